@@ -1,0 +1,402 @@
+"""Pins for the CPU oracle: every check here compares the oracle with something
+other than itself (a library routine, a closed form, finite differences, a
+token-by-token brute force, an algebraic invariant, counts printed by the paper
+or derived by hand).  No GPU, no HIP library."""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import dense_rollout as A
+from oracle import tree_direct as B
+from oracle import tree_layout as L
+from workloads import chain_tree, config_tree, make_inputs_numpy, random_tree
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _inputs(T, Hq, Hkv, d, seed):
+    x = make_inputs_numpy(T, Hq, Hkv, d, seed)
+    return (x["q"].astype(np.float64), x["k"].astype(np.float64),
+            x["v"].astype(np.float64), x["do"].astype(np.float64))
+
+
+# ---------------------------------------------------------------- brute force
+def _token_tables(parent, seg_len):
+    """Pure-python per-token tables built by walking parents token by token:
+    tok_node[t], and vis[t] = sorted list of visible key tokens (incl. t)."""
+    parent = [int(p) for p in parent]
+    seg_len = [int(s) for s in seg_len]
+    n = len(parent)
+    kids = {i: [] for i in range(n)}
+    roots = []
+    for i, p in enumerate(parent):
+        (roots if p < 0 else kids[p]).append(i)
+    first = {}
+    t = 0
+
+    def visit(u):
+        nonlocal t
+        first[u] = t
+        t += seg_len[u]
+        for c in sorted(kids[u]):
+            visit(c)
+    for r in sorted(roots):
+        visit(r)
+    vis = {}
+    for u in range(n):
+        above = []
+        a = parent[u]
+        while a >= 0:
+            above = list(range(first[a], first[a] + seg_len[a])) + above
+            a = parent[a]
+        for j in range(seg_len[u]):
+            vis[first[u] + j] = above + list(range(first[u], first[u] + j + 1))
+    return first, vis, t
+
+
+def _brute_forward(vis, q, k, v, scale, G):
+    T, Hq, d = q.shape
+    O = np.zeros((T, Hq, d))
+    LSE = np.zeros((T, Hq))
+    for t in range(T):
+        for h in range(Hq):
+            s = [scale * float(np.dot(q[t, h], k[j, h // G])) for j in vis[t]]
+            tot = sum(math.exp(x) for x in s)
+            LSE[t, h] = math.log(tot)
+            for x, j in zip(s, vis[t]):
+                O[t, h] += math.exp(x) / tot * v[j, h // G]
+    return O, LSE
+
+
+SMALL_TREES = [
+    ([-1], [5]),
+    ([-1, 0, 0], [3, 2, 4]),
+    ([-1, 0, 1, 1, 0], [2, 3, 1, 2, 3]),
+    ([2, 2, -1, 0, -1, 4], [2, 1, 3, 2, 2, 1]),       # ids out of DFS order, two roots
+]
+
+
+@pytest.mark.parametrize("parent,seg", SMALL_TREES)
+@pytest.mark.parametrize("Hq,Hkv", [(1, 1), (4, 2)])
+def test_forward_matches_token_by_token_brute_force(parent, seg, Hq, Hkv):
+    first, vis, T = _token_tables(parent, seg)
+    q, k, v, _ = _inputs(T, Hq, Hkv, 8, seed=11)
+    scale = 0.37
+    Ob, Lb = _brute_forward(vis, q, k, v, scale, Hq // Hkv)
+    Oa, La = A.forward(parent, seg, q, k, v, scale)
+    Od, Ld = B.forward(parent, seg, q, k, v, scale)
+    for O, Ls in ((Oa, La), (Od, Ld)):
+        assert np.abs(O - Ob).max() < 1e-12
+        assert np.abs(Ls - Lb).max() < 1e-12
+    # the oracle's own preorder agrees with the brute-force visit order
+    off, T2 = L.node_offsets(parent, seg)
+    assert T2 == T and all(int(off[u]) == first[u] for u in range(len(parent)))
+
+
+def test_all_tiny_trees_exhaustively():
+    """Every forest with <= 4 nodes and seg_len in {1,2}: A == B == brute force."""
+    import itertools
+    rng = np.random.default_rng(5)
+    count = 0
+    for n in range(1, 5):
+        for par in itertools.product(*[range(-1, i) for i in range(n)]):
+            for seg in itertools.product([1, 2], repeat=n):
+                if rng.random() > 0.25 and n == 4:
+                    continue
+                _, vis, T = _token_tables(par, seg)
+                q, k, v, _ = _inputs(T, 2, 1, 4, seed=count)
+                Ob, Lb = _brute_forward(vis, q, k, v, 0.5, 2)
+                Oa, La = A.forward(par, seg, q, k, v, 0.5)
+                Od, Ld = B.forward(par, seg, q, k, v, 0.5)
+                assert np.abs(Oa - Ob).max() < 1e-12 and np.abs(Od - Ob).max() < 1e-12
+                assert np.abs(La - Lb).max() < 1e-12 and np.abs(Ld - Lb).max() < 1e-12
+                count += 1
+    assert count > 100
+
+
+# ------------------------------------------------------------ library routine
+@pytest.mark.parametrize("Hq,Hkv", [(2, 2), (4, 2), (8, 2)])
+def test_chain_is_textbook_causal_attention_torch_sdpa(Hq, Hkv):
+    """A single-chain tree reduces to ordinary causal attention; torch's
+    scaled_dot_product_attention and its autograd are the outside reference."""
+    parent, seg = chain_tree([7, 1, 12, 5])
+    T, d = int(seg.sum()), 16
+    q, k, v, do = _inputs(T, Hq, Hkv, d, seed=3)
+    scale = 1.0 / math.sqrt(d)
+    G = Hq // Hkv
+    tq = torch.tensor(q.transpose(1, 0, 2), requires_grad=True)     # [H,T,d]
+    tk = torch.tensor(k.transpose(1, 0, 2), requires_grad=True)
+    tv = torch.tensor(v.transpose(1, 0, 2), requires_grad=True)
+    out = torch.nn.functional.scaled_dot_product_attention(
+        tq[None], tk.repeat_interleave(G, dim=0)[None], tv.repeat_interleave(G, dim=0)[None],
+        is_causal=True, scale=scale)[0]
+    out.backward(torch.tensor(do.transpose(1, 0, 2)))
+    ref = {"o": out.detach().numpy().transpose(1, 0, 2),
+           "dq": tq.grad.numpy().transpose(1, 0, 2),
+           "dk": tk.grad.numpy().transpose(1, 0, 2),
+           "dv": tv.grad.numpy().transpose(1, 0, 2)}
+    for mod in (A, B):
+        O, LSE = mod.forward(parent, seg, q, k, v, scale)
+        dQ, dK, dV = mod.backward(parent, seg, q, k, v, do, scale)
+        assert np.abs(O - ref["o"]).max() < 1e-12
+        assert np.abs(dQ - ref["dq"]).max() < 1e-11
+        assert np.abs(dK - ref["dk"]).max() < 1e-11
+        assert np.abs(dV - ref["dv"]).max() < 1e-11
+        # LSE against torch.logsumexp of the masked scores
+        s = scale * torch.einsum("htd,hsd->hts", tq.detach(), tk.detach().repeat_interleave(G, dim=0))
+        s = s.masked_fill(torch.triu(torch.ones(T, T, dtype=torch.bool), 1), -float("inf"))
+        assert np.abs(LSE - torch.logsumexp(s, -1).numpy().T).max() < 1e-12
+
+
+def test_tree_rows_equal_sdpa_on_each_expanded_rollout():
+    """O at every position a token occupies equals dense attention on that
+    rollout, with torch's routine (not the oracle's) doing the dense part."""
+    rng = np.random.default_rng(21)
+    parent, seg = random_tree(rng, 7, 5)
+    T = int(seg.sum())
+    q, k, v, _ = _inputs(T, 2, 1, 8, seed=4)
+    O, _ = B.forward(parent, seg, q, k, v, 0.3)
+    for idx in L.rollout_token_paths(parent, seg):
+        tq = torch.tensor(q[idx].transpose(1, 0, 2))[None]
+        tk = torch.tensor(k[idx].transpose(1, 0, 2)).repeat_interleave(2, dim=0)[None]
+        tv = torch.tensor(v[idx].transpose(1, 0, 2)).repeat_interleave(2, dim=0)[None]
+        ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True, scale=0.3)[0]
+        assert np.abs(O[idx] - ref.numpy().transpose(1, 0, 2)).max() < 1e-12
+
+
+# --------------------------------------------------------------- closed forms
+@pytest.mark.parametrize("mod", [A, B])
+def test_zero_keys_closed_form(mod):
+    """K = 0: every visible key gets the same weight, so LSE = ln(pos+1) and O is
+    the mean of V over the ancestor path; pins key-set size and membership."""
+    rng = np.random.default_rng(8)
+    parent, seg = random_tree(rng, 9, 6, n_roots=2)
+    _, vis, T = _token_tables(parent, seg)
+    q, _, v, _ = _inputs(T, 2, 2, 8, seed=9)
+    O, LSE = mod.forward(parent, seg, q, np.zeros((T, 2, 8)), v, 1.7)
+    for t in range(T):
+        assert abs(LSE[t, 0] - math.log(len(vis[t]))) < 1e-13
+        assert np.abs(O[t] - v[vis[t]].mean(axis=0)).max() < 1e-13
+
+
+@pytest.mark.parametrize("mod", [A, B])
+def test_first_token_and_constant_values(mod):
+    parent, seg, _ = config_tree(1)
+    seg = np.maximum(1, seg // 8)
+    T = int(seg.sum())
+    q, k, v, _ = _inputs(T, 4, 2, 8, seed=10)
+    O, LSE = mod.forward(parent, seg, q, k, v, 0.25)
+    # position 0 sees only itself
+    assert np.abs(O[0] - v[0].repeat(2, axis=0)).max() < 1e-14
+    assert np.abs(LSE[0] - 0.25 * np.einsum("hd,hd->h", q[0], k[0].repeat(2, axis=0))).max() < 1e-13
+    # V == c  =>  O == c
+    O2, _ = mod.forward(parent, seg, q, k, np.full_like(v, 3.5), 0.25)
+    assert np.abs(O2 - 3.5).max() < 1e-13
+
+
+# --------------------------------------------------------- finite differences
+def _objective(parent, seg, q, k, v, do, scale):
+    O, _ = B.forward(parent, seg, q, k, v, scale)
+    return float((O * do).sum())
+
+
+@pytest.mark.parametrize("mod", [A, B])
+def test_gradients_against_central_finite_differences(mod):
+    rng = np.random.default_rng(33)
+    parent, seg = random_tree(rng, 6, 4)
+    T = int(seg.sum())
+    q, k, v, do = _inputs(T, 4, 2, 6, seed=12)
+    scale = 0.41
+    dQ, dK, dV = mod.backward(parent, seg, q, k, v, do, scale)
+    eps = 1e-5
+    for name, arr, grad in (("q", q, dQ), ("k", k, dK), ("v", v, dV)):
+        for _ in range(25):
+            i = tuple(int(rng.integers(0, s)) for s in arr.shape)
+            old = arr[i]
+            arr[i] = old + eps
+            fp = _objective(parent, seg, q, k, v, do, scale)
+            arr[i] = old - eps
+            fm = _objective(parent, seg, q, k, v, do, scale)
+            arr[i] = old
+            fd = (fp - fm) / (2 * eps)
+            assert abs(fd - grad[i]) < 1e-7 * max(1.0, abs(fd)), (name, i, fd, grad[i])
+
+
+def test_forward_objective_used_for_fd_is_brute_force_checked():
+    """The finite-difference objective uses B.forward, itself pinned above; make
+    the dependency explicit on the same tree shape."""
+    rng = np.random.default_rng(33)
+    parent, seg = random_tree(rng, 6, 4)
+    _, vis, T = _token_tables(parent, seg)
+    q, k, v, _ = _inputs(T, 4, 2, 6, seed=12)
+    Ob, _ = _brute_forward(vis, q, k, v, 0.41, 2)
+    assert np.abs(B.forward(parent, seg, q, k, v, 0.41)[0] - Ob).max() < 1e-12
+
+
+# ----------------------------------------------------------------- invariants
+def test_A_equals_B_on_config1_and_random_trees():
+    parent, seg, _ = config_tree(1)
+    T = int(seg.sum())
+    q, k, v, do = _inputs(T, 4, 4, 16, seed=2001)
+    Oa, La, spread = A.forward(parent, seg, q, k, v, 0.25, return_spread=True)
+    Ob, Lb = B.forward(parent, seg, q, k, v, 0.25)
+    assert spread < 1e-12
+    assert np.abs(Oa - Ob).max() < 1e-12 and np.abs(La - Lb).max() < 1e-12
+    for a, b in zip(A.backward(parent, seg, q, k, v, do, 0.25), B.backward(parent, seg, q, k, v, do, 0.25)):
+        assert np.abs(a - b).max() < 1e-11
+    rng = np.random.default_rng(77)
+    for trial in range(6):
+        parent, seg = random_tree(rng, int(rng.integers(1, 12)), 7, n_roots=int(rng.integers(1, 3)))
+        T = int(seg.sum())
+        q, k, v, do = _inputs(T, 4, 2, 8, seed=100 + trial)
+        for a, b in zip(A.backward(parent, seg, q, k, v, do, 0.3), B.backward(parent, seg, q, k, v, do, 0.3)):
+            assert np.abs(a - b).max() < 1e-11
+
+
+def test_rollout_split_weights_do_not_matter():
+    """Summation over rollouts (equation 1): any split of a shared token's dO
+    over the rollouts containing it gives the same tree gradients."""
+    parent, seg, _ = config_tree(1)
+    seg = np.maximum(1, seg // 4)
+    T = int(seg.sum())
+    q, k, v, do = _inputs(T, 4, 2, 8, seed=13)
+    base = A.backward(parent, seg, q, k, v, do, 0.35)
+    rng = np.random.default_rng(14)
+    paths = L.rollout_token_paths(parent, seg)
+    raw = [rng.gamma(1.0, size=len(p)) for p in paths]
+    tot = np.zeros(T)
+    for p, r in zip(paths, raw):
+        tot[p] += r
+    weights = [r / tot[p] for p, r in zip(paths, raw)]
+    for a, b in zip(base, A.backward(parent, seg, q, k, v, do, 0.35, weights=weights)):
+        assert np.abs(a - b).max() < 1e-12
+
+
+@pytest.mark.parametrize("mod", [A, B])
+def test_softmax_and_gradient_identities(mod):
+    rng = np.random.default_rng(15)
+    parent, seg = random_tree(rng, 8, 6)
+    T = int(seg.sum())
+    q, k, v, do = _inputs(T, 4, 2, 8, seed=16)
+    dQ, dK, dV = mod.backward(parent, seg, q, k, v, do, 0.3)
+    # sum_k dV_k = sum_t dO_t per kv head (rows of P sum to one), q heads of a group added
+    assert np.abs(dV.sum(axis=0) - do.reshape(T, 2, 2, 8).sum(axis=(0, 2))).max() < 1e-11
+    # scores are bilinear in (q, k): sum_t q_t.dQ_t and sum_k k_k.dK_k both equal
+    # sum_{t,k} dS_tk * s_tk, per kv group
+    lhs = np.einsum("thd,thd->h", q, dQ).reshape(2, 2).sum(axis=1)
+    rhs = np.einsum("tgd,tgd->g", k, dK)
+    assert np.abs(lhs - rhs).max() < 1e-10
+    # linearity in dO
+    do2 = rng.standard_normal(do.shape)
+    g1 = mod.backward(parent, seg, q, k, v, do2, 0.3)
+    g12 = mod.backward(parent, seg, q, k, v, do + do2, 0.3)
+    for a, b, c in zip((dQ, dK, dV), g1, g12):
+        assert np.abs(a + b - c).max() < 1e-11
+
+
+def test_node_split_and_child_order_invariance():
+    """Splitting a segment into a unary chain, or renumbering children (another
+    valid DFS order, section 4), changes no per-token value."""
+    parent = np.array([-1, 0, 0, 1, 1], dtype=np.int32)
+    seg = np.array([6, 4, 5, 3, 2], dtype=np.int32)
+    T = int(seg.sum())
+    q, k, v, do = _inputs(T, 2, 1, 8, seed=17)
+    ref = B.forward(parent, seg, q, k, v, 0.3) + B.backward(parent, seg, q, k, v, do, 0.3)
+    # split node 0 (6 tokens) into 0:(2) -> 5:(4); children of 0 move under 5.
+    # preorder (ascending ids) would visit 5 after 1,2, so renumber to keep packing:
+    parent2 = np.array([-1, 0, 1, 1, 2, 2], dtype=np.int32)      # 0:2tok,1:4tok,(old1)->2,(old2)->3,(old3)->4,(old4)->5
+    seg2 = np.array([2, 4, 4, 5, 3, 2], dtype=np.int32)
+    # packed order of old tree: 0,1,3,4,2 ; new tree preorder: 0,1,2,4,5,3 -> same token order
+    out = B.forward(parent2, seg2, q, k, v, 0.3) + B.backward(parent2, seg2, q, k, v, do, 0.3)
+    for a, b in zip(ref, out):
+        assert np.abs(a - b).max() < 1e-12
+    # child order: swap ids of the two children of the root; tokens move, values follow
+    parent3 = np.array([-1, 0, 0, 2, 2], dtype=np.int32)         # old node 1 is now id 2, old 2 is id 1
+    seg3 = np.array([6, 5, 4, 3, 2], dtype=np.int32)
+    # old packed order of nodes: 0,1,3,4,2 ; new packed order: 0,(old2),(old1),(old3),(old4)
+    off_old, _ = L.node_offsets(parent, seg)
+    perm = np.concatenate([np.arange(off_old[u], off_old[u] + seg[u]) for u in (0, 2, 1, 3, 4)])
+    out3 = B.forward(parent3, seg3, q[perm], k[perm], v[perm], 0.3) + \
+        B.backward(parent3, seg3, q[perm], k[perm], v[perm], do[perm], 0.3)
+    for a, b in zip(ref, out3):
+        assert np.abs(a[perm] - b).max() < 1e-12
+
+
+def test_duplicate_leaf_doubles_ancestor_gradient_contribution():
+    parent = np.array([-1, 0], dtype=np.int32)
+    seg = np.array([5, 3], dtype=np.int32)
+    q, k, v, do = _inputs(8, 2, 1, 8, seed=18)
+    do[:5] = 0.0                                   # only the leaf carries loss
+    _, dK1, dV1 = B.backward(parent, seg, q, k, v, do, 0.3)
+    parent2 = np.array([-1, 0, 0], dtype=np.int32)
+    seg2 = np.array([5, 3, 3], dtype=np.int32)
+    dup = lambda x: np.concatenate([x, x[5:]])
+    _, dK2, dV2 = B.backward(parent2, seg2, dup(q), dup(k), dup(v), dup(do), 0.3)
+    assert np.abs(dK2[:5] - 2 * dK1[:5]).max() < 1e-12
+    assert np.abs(dV2[:5] - 2 * dV1[:5]).max() < 1e-12
+    assert np.abs(dK2[5:8] - dK1[5:]).max() < 1e-12 and np.abs(dK2[8:] - dK1[5:]).max() < 1e-12
+
+
+def test_sibling_independence():
+    parent = np.array([-1, 0, 0], dtype=np.int32)
+    seg = np.array([4, 3, 5], dtype=np.int32)
+    q, k, v, _ = _inputs(12, 2, 2, 8, seed=19)
+    O1, L1 = B.forward(parent, seg, q, k, v, 0.3)
+    k2, v2 = k.copy(), v.copy()
+    k2[4:7] += 1.0
+    v2[4:7] -= 2.0
+    O2, L2 = B.forward(parent, seg, q, k2, v2, 0.3)
+    assert np.array_equal(O1[7:], O2[7:]) and np.array_equal(L1[7:], L2[7:])
+    assert np.array_equal(O1[:4], O2[:4])
+    assert not np.allclose(O1[4:7], O2[4:7])
+
+
+# ------------------------------------------------------------------ statistics
+def test_config1_counts_golden():
+    want = {}
+    for line in open(os.path.join(GOLDEN, "config1_counts.txt")):
+        if line.strip() and not line.startswith("#"):
+            name, val = line.split()
+            want[name] = int(val)
+    parent, seg, _ = config_tree(1)
+    st = L.tree_stats(parent, seg)
+    for name, val in want.items():
+        assert st[name] == val, name
+    # unique pairs counted token by token
+    _, vis, T = _token_tables(parent, seg)
+    assert sum(len(vis[t]) for t in range(T)) == want["unique_pairs"]
+
+
+def test_compression_and_sharing_rate_golden():
+    """S = 1 - 1/C with the pairs printed in the caption of figure 1."""
+    for line in open(os.path.join(GOLDEN, "figure1_compression.txt")):
+        if line.strip() and not line.startswith("#"):
+            C, S = map(float, line.split())
+            assert abs((1.0 - 1.0 / C) * 100.0 - S) < 0.06
+    # a forest of n identical-prefix rollouts: C known in closed form
+    parent, seg = np.array([-1, 0, 0, 0]), np.array([10, 5, 5, 5])
+    st = L.tree_stats(parent, seg)
+    assert st["C_leaf"] == pytest.approx(45 / 25)
+    assert st["C_full"] == pytest.approx(55 / 25)
+    assert st["C_attn_leaf"] <= st["C_leaf"]
+
+
+def test_tree_token_identity_over_dfs_leaf_order():
+    """Unique tree tokens = |pi_1| + sum_i (|pi_i| - LCP(pi_{i-1}, pi_i)) over a
+    DFS leaf order (cost bookkeeping of the partitioning algorithm, appendix)."""
+    rng = np.random.default_rng(23)
+    for _ in range(10):
+        parent, seg = random_tree(rng, int(rng.integers(1, 15)), 6, shuffle_ids=False)
+        paths = L.rollout_token_paths(parent, seg)       # ascending leaf id; ids are a preorder here? not always
+        # sort rollouts lexicographically by their token-index vectors: a valid DFS order
+        paths = sorted(paths, key=lambda p: tuple(p.tolist()))
+        total = len(paths[0])
+        for a, b in zip(paths[:-1], paths[1:]):
+            lcp = 0
+            while lcp < min(len(a), len(b)) and a[lcp] == b[lcp]:
+                lcp += 1
+            total += len(b) - lcp
+        assert total == int(seg.sum())
