@@ -1,0 +1,183 @@
+/*
+ * dta.h - C ABI of the MI355X (gfx950) dynamic-tree-attention library.
+ *
+ * The library computes causal softmax attention, forward and backward, over a
+ * rollout prefix tree: every unique tree token's query attends to exactly the
+ * keys/values on its root-to-node path (whole ancestor segments plus the causal
+ * part of its own segment), so a prefix shared by many rollouts is computed
+ * once, and the gradient of a shared key/value is the sum over all descendant
+ * queries (paper section 3, problem formulation and equation 1; section 3.1,
+ * push / leaf / pop steps; pseudocode appendix, FWD and BWD primitives).
+ *
+ * General rules
+ *  - every function returns an int status (DTA_OK = 0, negative = error) unless
+ *    stated otherwise; nothing throws, nothing aborts;
+ *  - "host" pointers are ordinary CPU memory, "device" pointers are HIP device
+ *    memory of the current device; the caller owns every tensor and workspace,
+ *    the library owns only dta_tree_t objects;
+ *  - attention calls only enqueue work on the given HIP stream and do not
+ *    synchronise it.  The first attention call on a tree (or an explicit
+ *    dta_tree_attn_prepare) allocates and uploads the tree's device metadata
+ *    with a blocking copy; later calls allocate nothing;
+ *  - tensors are dense row-major [T, H, head_dim] with T = unique tree tokens in
+ *    the packed DFS order defined by dta_tree_build.
+ */
+#ifndef DTA_H_
+#define DTA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dta_tree dta_tree_t; /* opaque */
+
+enum {
+  DTA_OK = 0,
+  DTA_ERR_INVALID_ARG = -1, /* null pointer, n_nodes < 1, bad struct field         */
+  DTA_ERR_BAD_TREE = -2,    /* parent out of range / self parent / cycle / seg_len<1 / > 2^31-1 tokens */
+  DTA_ERR_UNSUPPORTED = -3, /* head_dim not in {64,128}, Hq % Hkv != 0, unknown dtype, bf16 with head_dim 64 */
+  DTA_ERR_ALLOC = -4,       /* host or device allocation failed                     */
+  DTA_ERR_HIP = -5,         /* a HIP runtime call or kernel launch failed           */
+  DTA_ERR_WORKSPACE = -6    /* workspace null or smaller than required              */
+};
+
+enum { DTA_F32 = 0, DTA_BF16 = 1 };
+
+/* Integer facts about a tree (all counts exact, int64). */
+typedef struct {
+  int64_t n_nodes;
+  int64_t n_tokens;            /* T: unique tree tokens = sum of seg_len                       */
+  int64_t n_leaves;            /* rollouts: every root-to-leaf path is one sequence            */
+  int64_t n_roots;
+  int64_t max_path_tokens;     /* longest rollout, in tokens                                   */
+  int64_t max_depth_nodes;     /* nodes on the deepest root-to-node path                       */
+  int64_t rollout_tokens;      /* sum of leaf path lengths (dense training would process this) */
+  int64_t rollout_tokens_full; /* same if every node ended a rollout (figure 1's full tree)    */
+  int64_t unique_pairs;        /* sum over tokens of (position+1): (query, visible key) pairs  */
+  int64_t dense_pairs;         /* sum over leaves of n(n+1)/2                                  */
+  int64_t dense_pairs_full;    /* same with every node ending a rollout                        */
+} dta_tree_info_t;
+
+/* Borrowed host pointers into the tree object, valid until dta_tree_destroy.
+ * Arrays indexed by node use the caller's node ids. */
+typedef struct {
+  const int32_t* dfs_order;        /* [n_nodes]   node id at each DFS preorder rank             */
+  const int64_t* node_offset;      /* [n_nodes]   first packed token index of the node          */
+  const int64_t* node_start_depth; /* [n_nodes]   tokens above the node on its root path        */
+  const int64_t* subtree_tokens;   /* [n_nodes]   tokens in the node and all its descendants;   */
+                                   /*             they occupy [offset, offset+subtree_tokens)   */
+  const int64_t* anc_ptr;          /* [n_nodes+1] CSR pointer into anc_seg_*                    */
+  const int64_t* anc_seg_off;      /* ancestor key intervals root->parent (packed token index), */
+  const int64_t* anc_seg_len;      /*   adjacent intervals merged when contiguous               */
+  const int32_t* token_kend;       /* [T] one past the last packed token that sees this key     */
+} dta_tree_layout_t;
+
+/* Tile schedule statistics for one head configuration (integer, host only). */
+typedef struct {
+  int64_t fwd_q_tile_tokens;   /* query tokens per forward work item                          */
+  int64_t fwd_work_items;      /* forward query tiles (per kv head)                           */
+  int64_t fwd_tile_pairs;      /* (padded query rows) x (keys streamed), summed over tiles    */
+  int64_t bwd_kv_tile_tokens;  /* keys per backward dK/dV work item                           */
+  int64_t bwd_work_items;
+  int64_t bwd_tile_pairs;      /* (padded key cols) x (query rows streamed)                   */
+} dta_schedule_info_t;
+
+typedef struct {
+  int32_t n_q_heads;
+  int32_t n_kv_heads;   /* must divide n_q_heads; q head h uses kv head h / (n_q_heads/n_kv_heads) */
+  int32_t head_dim;     /* 64 or 128 (DTA_F32), 128 (DTA_BF16)                                     */
+  float softmax_scale;  /* multiplies q.k before the softmax                                       */
+  int32_t dtype;        /* DTA_F32 or DTA_BF16: element type of q,k,v,o,dO,dq,dk,dv                */
+} dta_attn_params_t;
+
+/*
+ * dta_tree_build - tree metadata from (parent, seg_len); host only, integer only.
+ * A node is a token segment; parent[i] = -1 marks a root (several roots = a
+ * forest of independent trees); seg_len[i] >= 1 tokens (paper section 3: nodes
+ * are token segments, root-to-leaf paths are rollouts; path length is counted
+ * in tokens).  Nodes are packed in DFS preorder, roots and children in
+ * ascending node id (the paper leaves the DFS order free, section 4), so a
+ * subtree is one contiguous token range.
+ *   parent, seg_len : host, [n_nodes], read only during the call.
+ *   flags           : must be 0.
+ *   out             : receives a new tree; free it with dta_tree_destroy.
+ * Errors: INVALID_ARG (null, n_nodes < 1, flags != 0), BAD_TREE, ALLOC.
+ */
+int dta_tree_build(const int32_t* parent, const int32_t* seg_len, int32_t n_nodes,
+                   uint32_t flags, dta_tree_t** out);
+
+/* Counts for reporting: C = rollout_tokens / n_tokens is the compression rate
+ * of the paper's figure 1, S = 1 - 1/C its prefix-sharing rate. */
+int dta_tree_info(const dta_tree_t* tree, dta_tree_info_t* out);
+
+/* Packed layout and per-node ancestor-segment lists (borrowed host pointers). */
+int dta_tree_layout(const dta_tree_t* tree, dta_tree_layout_t* out);
+
+/* Builds (and caches in the tree) the DFS tile schedule for this head
+ * configuration and reports its size.  Host only. */
+int dta_tree_schedule_info(dta_tree_t* tree, const dta_attn_params_t* params,
+                           dta_schedule_info_t* out);
+
+/* Frees host and device memory of the tree.  NULL is allowed. */
+void dta_tree_destroy(dta_tree_t* tree);
+
+/* Bytes of device workspace dta_tree_attn_fwd (is_bwd = 0) or dta_tree_attn_bwd
+ * (is_bwd != 0) needs; 0 on invalid arguments.  The workspace must be 256-byte
+ * aligned; its contents need not be preserved between calls. */
+size_t dta_tree_attn_workspace_bytes(const dta_tree_t* tree, const dta_attn_params_t* params,
+                                     int is_bwd);
+
+/* Optional: allocate and upload the tree's device metadata for this head
+ * configuration now (blocking), so that later attention calls only enqueue. */
+int dta_tree_attn_prepare(dta_tree_t* tree, const dta_attn_params_t* params);
+
+/*
+ * dta_tree_attn_fwd - forward tree attention (the attention inside the paper's
+ * FWD primitive, for every segment of the tree in one pass).
+ * For token t, q head h, kv head g = h / (Hq/Hkv), with anc(t) the keys on t's
+ * root path up to and including t:
+ *   s_k = softmax_scale * q[t,h] . k[k,g]          for k in anc(t)
+ *   lse[t,h] = ln sum_k exp(s_k)
+ *   o[t,h]   = sum_k exp(s_k - lse[t,h]) * v[k,g]
+ *   q : device [T,Hq,d]   k,v : device [T,Hkv,d]   (dtype per params)
+ *   o : device [T,Hq,d] out, same dtype (round to nearest even)
+ *   lse : device [T,Hq] fp32 out (natural log)
+ *   workspace : device, >= dta_tree_attn_workspace_bytes(tree, params, 0) (may be NULL if that is 0)
+ *   hip_stream : a hipStream_t (NULL = default stream)
+ * bf16 mode multiplies in bf16 on the matrix cores and accumulates / does the
+ * softmax in fp32; fp32 mode is fp32 throughout.
+ */
+int dta_tree_attn_fwd(dta_tree_t* tree, const dta_attn_params_t* params, const void* q,
+                      const void* k, const void* v, void* o, float* lse, void* workspace,
+                      size_t workspace_bytes, void* hip_stream);
+
+/*
+ * dta_tree_attn_bwd - backward tree attention (the attention inside the paper's
+ * BWD primitive; gradients of all descendant rollouts are accumulated into a
+ * shared key/value, pop step of section 3.1 and equation 1).
+ * d_o is the upstream gradient per TREE token, already summed over the rollouts
+ * sharing the token.  With p_tk = exp(s_tk - lse_t), D_t = d_o_t . o_t,
+ * ds_tk = p_tk (d_o_t . v_k - D_t):
+ *   dq[t,h] = scale * sum_{k in anc(t)} ds_tk k_k
+ *   dk[k,g] = scale * sum_{h in group g} sum_{t : k in anc(t)} ds_tk q_t
+ *   dv[k,g] =         sum_{h in group g} sum_{t : k in anc(t)} p_tk d_o_t
+ *   q,k,v,o,d_o : device inputs as in forward; lse : device [T,Hq] fp32 from forward
+ *   dq : device [T,Hq,d] out;  dk, dv : device [T,Hkv,d] out.  All three are
+ *        OVERWRITTEN (each element written exactly once, no atomics).
+ *   workspace : device, >= dta_tree_attn_workspace_bytes(tree, params, 1)
+ */
+int dta_tree_attn_bwd(dta_tree_t* tree, const dta_attn_params_t* params, const void* q,
+                      const void* k, const void* v, const void* o, const float* lse,
+                      const void* d_o, void* dq, void* dk, void* dv, void* workspace,
+                      size_t workspace_bytes, void* hip_stream);
+
+/* Static, human-readable name of a status code. */
+const char* dta_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DTA_H_ */

@@ -1,0 +1,160 @@
+// C-ABI attention entry points: argument checks, device metadata upload and
+// dispatch to the kernel launchers.  See include/dta.h for the contract.
+#include <hip/hip_runtime.h>
+
+#include <new>
+
+#include "dta_internal.h"
+
+namespace {
+
+inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+size_t delta_bytes(const dta_tree* tree, const dta_attn_params_t* p) {
+  return round_up((size_t)tree->info.n_tokens * (size_t)p->n_q_heads * sizeof(float), 256);
+}
+
+template <typename T>
+int upload(const std::vector<T>& host, T** dev) {
+  if (*dev) {
+    (void)hipFree(*dev);
+    *dev = nullptr;
+  }
+  size_t bytes = host.size() * sizeof(T);
+  if (bytes == 0) bytes = sizeof(T);
+  if (hipMalloc((void**)dev, bytes) != hipSuccess) {
+    *dev = nullptr;
+    return DTA_ERR_ALLOC;
+  }
+  if (!host.empty() &&
+      hipMemcpy(*dev, host.data(), host.size() * sizeof(T), hipMemcpyHostToDevice) != hipSuccess)
+    return DTA_ERR_HIP;
+  return DTA_OK;
+}
+
+// Makes sure the schedule for (bm, bn) and kend[] are resident on the current
+// device.  Takes the tree lock; blocking on first use, a no-op afterwards.
+int ensure_device(dta_tree* tree, const dta::TileChoice& tc, dta::Schedule** out) {
+  std::lock_guard<std::mutex> lock(tree->mu);
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return DTA_ERR_HIP;
+  dta::Schedule* s;
+  try {
+    s = &dta::get_schedule(tree, tc.bm, tc.bn);
+  } catch (const std::bad_alloc&) {
+    return DTA_ERR_ALLOC;
+  }
+  int st;
+  if (tree->kend_device != dev) {
+    if ((st = upload(tree->token_kend, &tree->d_token_kend)) != DTA_OK) return st;
+    tree->kend_device = dev;
+  }
+  if (s->device != dev) {
+    if ((st = upload(s->q_tiles, &s->d_q_tiles)) != DTA_OK) return st;
+    if ((st = upload(s->segs, &s->d_segs)) != DTA_OK) return st;
+    if ((st = upload(s->kv_tiles, &s->d_kv_tiles)) != DTA_OK) return st;
+    s->device = dev;
+  }
+  *out = s;
+  return DTA_OK;
+}
+
+inline bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
+
+}  // namespace
+
+extern "C" {
+
+void dta_tree_destroy(dta_tree_t* tree) {
+  if (!tree) return;
+  if (tree->d_token_kend) (void)hipFree(tree->d_token_kend);
+  for (auto& kv : tree->schedules) {
+    dta::Schedule& s = kv.second;
+    if (s.d_q_tiles) (void)hipFree(s.d_q_tiles);
+    if (s.d_segs) (void)hipFree(s.d_segs);
+    if (s.d_kv_tiles) (void)hipFree(s.d_kv_tiles);
+  }
+  delete tree;
+}
+
+size_t dta_tree_attn_workspace_bytes(const dta_tree_t* tree, const dta_attn_params_t* params,
+                                     int is_bwd) {
+  if (!tree || dta::validate_params(params) != DTA_OK) return 0;
+  return is_bwd ? delta_bytes(tree, params) : 0;
+}
+
+int dta_tree_attn_prepare(dta_tree_t* tree, const dta_attn_params_t* params) {
+  if (!tree) return DTA_ERR_INVALID_ARG;
+  dta::TileChoice tc;
+  int st = dta::choose_tiles(params, &tc);
+  if (st != DTA_OK) return st;
+  dta::Schedule* s = nullptr;
+  return ensure_device(tree, tc, &s);
+}
+
+int dta_tree_attn_fwd(dta_tree_t* tree, const dta_attn_params_t* params, const void* q,
+                      const void* k, const void* v, void* o, float* lse, void* workspace,
+                      size_t workspace_bytes, void* hip_stream) {
+  (void)workspace;
+  (void)workspace_bytes;
+  if (!tree || !params) return DTA_ERR_INVALID_ARG;
+  dta::TileChoice tc;
+  int st = dta::choose_tiles(params, &tc);
+  if (st != DTA_OK) return st;
+  if (!q || !k || !v || !o || !lse) return DTA_ERR_INVALID_ARG;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse))
+    return DTA_ERR_INVALID_ARG;
+  dta::Schedule* s = nullptr;
+  if ((st = ensure_device(tree, tc, &s)) != DTA_OK) return st;
+  dta::LaunchArgs a{};
+  a.tree = tree;
+  a.sched = s;
+  a.d_kend = tree->d_token_kend;
+  a.p = *params;
+  a.tc = tc;
+  a.q = q;
+  a.k = k;
+  a.v = v;
+  a.o_out = o;
+  a.lse_out = lse;
+  a.stream = hip_stream;
+  return params->dtype == DTA_F32 ? dta::launch_fwd_f32(a) : dta::launch_fwd_bf16(a);
+}
+
+int dta_tree_attn_bwd(dta_tree_t* tree, const dta_attn_params_t* params, const void* q,
+                      const void* k, const void* v, const void* o, const float* lse,
+                      const void* d_o, void* dq, void* dk, void* dv, void* workspace,
+                      size_t workspace_bytes, void* hip_stream) {
+  if (!tree || !params) return DTA_ERR_INVALID_ARG;
+  dta::TileChoice tc;
+  int st = dta::choose_tiles(params, &tc);
+  if (st != DTA_OK) return st;
+  if (!q || !k || !v || !o || !lse || !d_o || !dq || !dk || !dv) return DTA_ERR_INVALID_ARG;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse) ||
+      misaligned(d_o) || misaligned(dq) || misaligned(dk) || misaligned(dv))
+    return DTA_ERR_INVALID_ARG;
+  if (!workspace || workspace_bytes < delta_bytes(tree, params) || ((uintptr_t)workspace & 255u))
+    return DTA_ERR_WORKSPACE;
+  dta::Schedule* s = nullptr;
+  if ((st = ensure_device(tree, tc, &s)) != DTA_OK) return st;
+  dta::LaunchArgs a{};
+  a.tree = tree;
+  a.sched = s;
+  a.d_kend = tree->d_token_kend;
+  a.p = *params;
+  a.tc = tc;
+  a.q = q;
+  a.k = k;
+  a.v = v;
+  a.o = o;
+  a.d_o = d_o;
+  a.lse_in = lse;
+  a.dq = dq;
+  a.dk = dk;
+  a.dv = dv;
+  a.delta = (float*)workspace;
+  a.stream = hip_stream;
+  return params->dtype == DTA_F32 ? dta::launch_bwd_f32(a) : dta::launch_bwd_bf16(a);
+}
+
+}  // extern "C"

@@ -1,0 +1,110 @@
+// Internal declarations shared by the host tree builder, the C-ABI entry points
+// and the kernel launchers.  Not part of the public interface.
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+#include <map>
+#include <mutex>
+#include <vector>
+
+#include "dta.h"
+
+namespace dta {
+
+// One forward / dQ work item: BM consecutive packed query tokens [t0, t1).  The
+// keys they can see are the key intervals segs[seg_begin, seg_end) that lie
+// before t0 (pieces of t0's root path) followed by the tile's own range, which
+// always needs the visibility mask  k <= t < kend[k].
+struct QTile {
+  int32_t t0, t1;
+  int32_t seg_begin, seg_end;
+};
+
+// A key interval [start, end) in packed token coordinates.  full != 0 means
+// every query row of the tile sees every key of the interval (no mask needed).
+struct KeySeg {
+  int32_t start, end;
+  int32_t full;
+  int32_t pad;
+};
+
+// One dK/dV work item: BN consecutive packed keys [k0, k1).  The queries that
+// see at least one of them are exactly [k0, q_end); rows in [k1, q_full_end)
+// see all of them, every other row needs the visibility mask.
+struct KvTile {
+  int32_t k0, k1;
+  int32_t q_end;
+  int32_t q_full_end;
+};
+
+// Tile schedule for one (BM, BN) choice: host vectors, and device copies made on
+// first use.  Work items are stored longest first so that the hardware block
+// dispatcher, which hands out blocks in index order, balances the CUs.
+struct Schedule {
+  int bm = 0, bn = 0;
+  std::vector<QTile> q_tiles;
+  std::vector<KeySeg> segs;
+  std::vector<KvTile> kv_tiles;
+  int64_t fwd_tile_pairs = 0, bwd_tile_pairs = 0;
+  // device copies (owned; freed with the tree)
+  int device = -1;
+  QTile* d_q_tiles = nullptr;
+  KeySeg* d_segs = nullptr;
+  KvTile* d_kv_tiles = nullptr;
+};
+
+}  // namespace dta
+
+struct dta_tree {
+  int32_t n_nodes = 0;
+  std::vector<int32_t> parent, seg_len;
+  std::vector<int32_t> dfs_order;
+  std::vector<int64_t> node_offset, node_start_depth, subtree_tokens;
+  std::vector<int64_t> anc_ptr, anc_seg_off, anc_seg_len;
+  std::vector<int32_t> token_kend;   // [T]
+  std::vector<int32_t> token_node;   // [T] node id owning each packed token
+  dta_tree_info_t info{};
+  // schedules keyed by (bm << 16 | bn)
+  std::map<uint32_t, dta::Schedule> schedules;
+  int32_t* d_token_kend = nullptr;
+  int kend_device = -1;
+  std::mutex mu;
+};
+
+namespace dta {
+
+// Host: build (or fetch) the schedule for tile sizes (bm, bn).
+Schedule& get_schedule(dta_tree* tree, int bm, int bn);
+
+// Tile sizes the kernels use for a head configuration.
+struct TileChoice {
+  int bm;       // query tokens per forward / dQ work item
+  int bn;       // keys per dK/dV work item
+  int hb;       // q heads of one kv group handled by one forward block
+  int hblocks;  // blocks per (tile, kv head) = group size / hb
+};
+int choose_tiles(const dta_attn_params_t* p, TileChoice* out);
+int validate_params(const dta_attn_params_t* p);
+
+struct LaunchArgs {
+  const dta_tree* tree;
+  const Schedule* sched;
+  const int32_t* d_kend;
+  dta_attn_params_t p;
+  TileChoice tc;
+  const void *q, *k, *v, *o, *d_o;
+  const float* lse_in;
+  void *o_out, *dq, *dk, *dv;
+  float* lse_out;
+  float* delta;  // workspace: D[t,h] = dO.O
+  void* stream;
+};
+
+// Kernel launchers (defined in the .hip files); return a DTA status.
+int launch_fwd_f32(const LaunchArgs& a);
+int launch_bwd_f32(const LaunchArgs& a);
+int launch_fwd_bf16(const LaunchArgs& a);
+int launch_bwd_bf16(const LaunchArgs& a);
+
+}  // namespace dta

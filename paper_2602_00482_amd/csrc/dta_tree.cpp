@@ -1,0 +1,344 @@
+// Host side of the library: tree metadata (dta_tree_build and friends) and the
+// DFS tile schedule.  Integer work only; nothing here touches the GPU.
+//
+// The tree is the rollout prefix tree of paper section 3 (problem formulation):
+// nodes are token segments, root-to-leaf paths are rollouts, and path length is
+// counted in tokens.  Nodes are packed in DFS preorder (any DFS order is valid,
+// section 4); in that order the tokens that can see key k form the contiguous
+// range [k, kend[k]) where kend[k] is the end of the subtree of k's node, which
+// is what the kernels use as their visibility mask.
+#include <algorithm>
+#include <cstring>
+#include <limits>
+#include <new>
+#include <numeric>
+
+#include "dta_internal.h"
+
+namespace {
+
+int build_impl(const int32_t* parent, const int32_t* seg_len, int32_t n, dta_tree* t) {
+  t->n_nodes = n;
+  t->parent.assign(parent, parent + n);
+  t->seg_len.assign(seg_len, seg_len + n);
+
+  int64_t total = 0;
+  for (int32_t i = 0; i < n; ++i) {
+    if (parent[i] < -1 || parent[i] >= n || parent[i] == i) return DTA_ERR_BAD_TREE;
+    if (seg_len[i] < 1) return DTA_ERR_BAD_TREE;
+    total += seg_len[i];
+  }
+  // leave room so that tile-padded indices still fit in int32
+  if (total > (int64_t)std::numeric_limits<int32_t>::max() - 4096) return DTA_ERR_BAD_TREE;
+
+  // children in CSR form; filling in ascending i keeps each list ascending
+  std::vector<int32_t> child_ptr(n + 1, 0), child(n > 0 ? n : 1), roots;
+  for (int32_t i = 0; i < n; ++i) {
+    if (parent[i] >= 0) child_ptr[parent[i] + 1]++;
+    else roots.push_back(i);
+  }
+  for (int32_t i = 0; i < n; ++i) child_ptr[i + 1] += child_ptr[i];
+  {
+    std::vector<int32_t> fill(child_ptr.begin(), child_ptr.end() - 1);
+    for (int32_t i = 0; i < n; ++i)
+      if (parent[i] >= 0) child[fill[parent[i]]++] = i;
+  }
+
+  // iterative preorder; nodes on a parent cycle are never reached from a root
+  t->dfs_order.clear();
+  t->dfs_order.reserve(n);
+  {
+    std::vector<int32_t> stack;
+    for (auto it = roots.rbegin(); it != roots.rend(); ++it) stack.push_back(*it);
+    while (!stack.empty()) {
+      int32_t u = stack.back();
+      stack.pop_back();
+      t->dfs_order.push_back(u);
+      for (int32_t c = child_ptr[u + 1] - 1; c >= child_ptr[u]; --c) stack.push_back(child[c]);
+    }
+  }
+  if ((int32_t)t->dfs_order.size() != n) return DTA_ERR_BAD_TREE;
+
+  t->node_offset.assign(n, 0);
+  t->node_start_depth.assign(n, 0);
+  t->subtree_tokens.assign(n, 0);
+  std::vector<int32_t> depth_nodes(n, 1);
+  int64_t pos = 0;
+  for (int32_t r = 0; r < n; ++r) {
+    int32_t u = t->dfs_order[r];
+    t->node_offset[u] = pos;
+    pos += seg_len[u];
+    int32_t p = parent[u];
+    if (p >= 0) {
+      t->node_start_depth[u] = t->node_start_depth[p] + seg_len[p];
+      depth_nodes[u] = depth_nodes[p] + 1;
+    }
+  }
+  for (int32_t r = n - 1; r >= 0; --r) {
+    int32_t u = t->dfs_order[r];
+    t->subtree_tokens[u] += seg_len[u];
+    if (parent[u] >= 0) t->subtree_tokens[parent[u]] += t->subtree_tokens[u];
+  }
+
+  // per-node ancestor key intervals, root first, merged when contiguous
+  t->anc_ptr.assign(n + 1, 0);
+  t->anc_seg_off.clear();
+  t->anc_seg_len.clear();
+  {
+    std::vector<int32_t> path;
+    for (int32_t u = 0; u < n; ++u) {
+      path.clear();
+      for (int32_t a = parent[u]; a >= 0; a = parent[a]) path.push_back(a);
+      size_t first = t->anc_seg_off.size();
+      for (auto it = path.rbegin(); it != path.rend(); ++it) {
+        int64_t off = t->node_offset[*it], len = seg_len[*it];
+        if (t->anc_seg_off.size() > first &&
+            t->anc_seg_off.back() + t->anc_seg_len.back() == off) {
+          t->anc_seg_len.back() += len;
+        } else {
+          t->anc_seg_off.push_back(off);
+          t->anc_seg_len.push_back(len);
+        }
+      }
+      t->anc_ptr[u + 1] = (int64_t)t->anc_seg_off.size();
+    }
+  }
+
+  t->token_kend.resize((size_t)total);
+  t->token_node.resize((size_t)total);
+  for (int32_t u = 0; u < n; ++u) {
+    int64_t off = t->node_offset[u];
+    int32_t kend = (int32_t)(off + t->subtree_tokens[u]);
+    for (int32_t j = 0; j < seg_len[u]; ++j) {
+      t->token_kend[(size_t)(off + j)] = kend;
+      t->token_node[(size_t)(off + j)] = u;
+    }
+  }
+
+  dta_tree_info_t& inf = t->info;
+  std::memset(&inf, 0, sizeof(inf));
+  inf.n_nodes = n;
+  inf.n_tokens = total;
+  inf.n_roots = (int64_t)roots.size();
+  for (int32_t u = 0; u < n; ++u) {
+    int64_t len = seg_len[u], sd = t->node_start_depth[u], end = sd + len;
+    bool leaf = child_ptr[u + 1] == child_ptr[u];
+    inf.unique_pairs += len * sd + len * (len + 1) / 2;
+    inf.rollout_tokens_full += end;
+    inf.dense_pairs_full += end * (end + 1) / 2;
+    if (leaf) {
+      inf.n_leaves++;
+      inf.rollout_tokens += end;
+      inf.dense_pairs += end * (end + 1) / 2;
+    }
+    inf.max_path_tokens = std::max(inf.max_path_tokens, end);
+    inf.max_depth_nodes = std::max<int64_t>(inf.max_depth_nodes, depth_nodes[u]);
+  }
+  return DTA_OK;
+}
+
+}  // namespace
+
+namespace dta {
+
+// Both work lists cut the packed token order into fixed runs of bm (bn) tokens,
+// whatever the node boundaries.  A tile pays for all of its padded rows anyway,
+// and the keys (queries) a run of consecutive DFS tokens needs are the union of
+// nested / adjacent intervals, never more than the sum over separate per-node
+// tiles, so cutting at node boundaries could only add work.  What a mixed tile
+// must not do is let a row see a key outside its own root path: the kernels
+// mask with kend[] wherever a key interval is not visible to every row.
+Schedule& get_schedule(dta_tree* tree, int bm, int bn) {
+  uint32_t key = ((uint32_t)bm << 16) | (uint32_t)bn;
+  auto it = tree->schedules.find(key);
+  if (it != tree->schedules.end()) return it->second;
+  Schedule& s = tree->schedules[key];
+  s.bm = bm;
+  s.bn = bn;
+  const int64_t T = tree->info.n_tokens;
+  const auto& parent = tree->parent;
+
+  // ---- query tiles (forward and dQ)
+  std::vector<int64_t> cost;
+  std::vector<int32_t> path;
+  for (int64_t t0 = 0; t0 < T; t0 += bm) {
+    int64_t t1 = std::min<int64_t>(T, t0 + bm);
+    QTile qt;
+    qt.t0 = (int32_t)t0;
+    qt.t1 = (int32_t)t1;
+    qt.seg_begin = (int32_t)s.segs.size();
+    int32_t u0 = tree->token_node[(size_t)t0];
+    path.clear();
+    for (int32_t a = parent[u0]; a >= 0; a = parent[a]) path.push_back(a);
+    int64_t keys = t1 - t0;
+    auto add = [&](int64_t start, int64_t end, int64_t kend) {
+      int32_t full = kend >= t1 ? 1 : 0;
+      if ((int32_t)s.segs.size() > qt.seg_begin && s.segs.back().end == start &&
+          s.segs.back().full == full) {
+        s.segs.back().end = (int32_t)end;
+      } else {
+        s.segs.push_back(KeySeg{(int32_t)start, (int32_t)end, full, 0});
+      }
+      keys += end - start;
+    };
+    for (auto a = path.rbegin(); a != path.rend(); ++a) {
+      int64_t off = tree->node_offset[*a];
+      add(off, off + tree->seg_len[*a], off + tree->subtree_tokens[*a]);
+    }
+    int64_t off0 = tree->node_offset[u0];
+    if (t0 > off0) add(off0, t0, off0 + tree->subtree_tokens[u0]);
+    qt.seg_end = (int32_t)s.segs.size();
+    s.q_tiles.push_back(qt);
+    cost.push_back(keys);
+    s.fwd_tile_pairs += keys * bm;
+  }
+  {
+    std::vector<size_t> order(s.q_tiles.size());
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(),
+                     [&](size_t a, size_t b) { return cost[a] > cost[b]; });
+    std::vector<QTile> sorted;
+    sorted.reserve(order.size());
+    for (size_t i : order) sorted.push_back(s.q_tiles[i]);
+    s.q_tiles.swap(sorted);
+  }
+
+  // ---- key tiles (dK/dV)
+  cost.clear();
+  for (int64_t k0 = 0; k0 < T; k0 += bn) {
+    int64_t k1 = std::min<int64_t>(T, k0 + bn);
+    int32_t mx = 0, mn = std::numeric_limits<int32_t>::max();
+    for (int64_t k = k0; k < k1; ++k) {
+      mx = std::max(mx, tree->token_kend[(size_t)k]);
+      mn = std::min(mn, tree->token_kend[(size_t)k]);
+    }
+    s.kv_tiles.push_back(KvTile{(int32_t)k0, (int32_t)k1, mx, mn});
+    cost.push_back(mx - k0);
+    s.bwd_tile_pairs += (int64_t)(mx - k0) * bn;
+  }
+  {
+    std::vector<size_t> order(s.kv_tiles.size());
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(),
+                     [&](size_t a, size_t b) { return cost[a] > cost[b]; });
+    std::vector<KvTile> sorted;
+    sorted.reserve(order.size());
+    for (size_t i : order) sorted.push_back(s.kv_tiles[i]);
+    s.kv_tiles.swap(sorted);
+  }
+  return s;
+}
+
+int validate_params(const dta_attn_params_t* p) {
+  if (!p) return DTA_ERR_INVALID_ARG;
+  if (p->n_q_heads < 1 || p->n_kv_heads < 1) return DTA_ERR_INVALID_ARG;
+  if (!(p->softmax_scale == p->softmax_scale)) return DTA_ERR_INVALID_ARG;  // NaN
+  if (p->n_q_heads % p->n_kv_heads != 0) return DTA_ERR_UNSUPPORTED;
+  if (p->dtype == DTA_F32) {
+    if (p->head_dim != 64 && p->head_dim != 128) return DTA_ERR_UNSUPPORTED;
+  } else if (p->dtype == DTA_BF16) {
+    if (p->head_dim != 128) return DTA_ERR_UNSUPPORTED;
+  } else {
+    return DTA_ERR_UNSUPPORTED;
+  }
+  return DTA_OK;
+}
+
+int choose_tiles(const dta_attn_params_t* p, TileChoice* out) {
+  int st = validate_params(p);
+  if (st != DTA_OK) return st;
+  int G = p->n_q_heads / p->n_kv_heads;
+  if (p->dtype == DTA_F32) {
+    out->bm = 64;
+    out->bn = 64;
+    out->hb = 1;
+    out->hblocks = G;
+  } else {
+    // four waves per block: hb q heads of the group x (4/hb) 64-row query blocks
+    int hb = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
+    out->hb = hb;
+    out->hblocks = G / hb;
+    out->bm = 64 * (4 / hb);
+    out->bn = 128;
+  }
+  return DTA_OK;
+}
+
+}  // namespace dta
+
+extern "C" {
+
+int dta_tree_build(const int32_t* parent, const int32_t* seg_len, int32_t n_nodes,
+                   uint32_t flags, dta_tree_t** out) {
+  if (out) *out = nullptr;
+  if (!parent || !seg_len || !out || n_nodes < 1 || flags != 0) return DTA_ERR_INVALID_ARG;
+  dta_tree* t = new (std::nothrow) dta_tree();
+  if (!t) return DTA_ERR_ALLOC;
+  int st;
+  try {
+    st = build_impl(parent, seg_len, n_nodes, t);
+  } catch (const std::bad_alloc&) {
+    st = DTA_ERR_ALLOC;
+  }
+  if (st != DTA_OK) {
+    delete t;
+    return st;
+  }
+  *out = t;
+  return DTA_OK;
+}
+
+int dta_tree_info(const dta_tree_t* tree, dta_tree_info_t* out) {
+  if (!tree || !out) return DTA_ERR_INVALID_ARG;
+  *out = tree->info;
+  return DTA_OK;
+}
+
+int dta_tree_layout(const dta_tree_t* tree, dta_tree_layout_t* out) {
+  if (!tree || !out) return DTA_ERR_INVALID_ARG;
+  out->dfs_order = tree->dfs_order.data();
+  out->node_offset = tree->node_offset.data();
+  out->node_start_depth = tree->node_start_depth.data();
+  out->subtree_tokens = tree->subtree_tokens.data();
+  out->anc_ptr = tree->anc_ptr.data();
+  out->anc_seg_off = tree->anc_seg_off.data();
+  out->anc_seg_len = tree->anc_seg_len.data();
+  out->token_kend = tree->token_kend.data();
+  return DTA_OK;
+}
+
+int dta_tree_schedule_info(dta_tree_t* tree, const dta_attn_params_t* params,
+                           dta_schedule_info_t* out) {
+  if (!tree || !out) return DTA_ERR_INVALID_ARG;
+  dta::TileChoice tc;
+  int st = dta::choose_tiles(params, &tc);
+  if (st != DTA_OK) return st;
+  try {
+    std::lock_guard<std::mutex> lock(tree->mu);
+    dta::Schedule& s = dta::get_schedule(tree, tc.bm, tc.bn);
+    out->fwd_q_tile_tokens = tc.bm;
+    out->fwd_work_items = (int64_t)s.q_tiles.size();
+    out->fwd_tile_pairs = s.fwd_tile_pairs;
+    out->bwd_kv_tile_tokens = tc.bn;
+    out->bwd_work_items = (int64_t)s.kv_tiles.size();
+    out->bwd_tile_pairs = s.bwd_tile_pairs;
+  } catch (const std::bad_alloc&) {
+    return DTA_ERR_ALLOC;
+  }
+  return DTA_OK;
+}
+
+const char* dta_status_string(int status) {
+  switch (status) {
+    case DTA_OK: return "DTA_OK";
+    case DTA_ERR_INVALID_ARG: return "DTA_ERR_INVALID_ARG";
+    case DTA_ERR_BAD_TREE: return "DTA_ERR_BAD_TREE";
+    case DTA_ERR_UNSUPPORTED: return "DTA_ERR_UNSUPPORTED";
+    case DTA_ERR_ALLOC: return "DTA_ERR_ALLOC";
+    case DTA_ERR_HIP: return "DTA_ERR_HIP";
+    case DTA_ERR_WORKSPACE: return "DTA_ERR_WORKSPACE";
+    default: return "DTA_ERR_UNKNOWN";
+  }
+}
+
+}  // extern "C"

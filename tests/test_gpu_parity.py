@@ -1,0 +1,81 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 CPU oracle,
+element by element on the same seeded inputs.
+
+Tolerances are the ones the task states: max|err| / max|ref| <= 1e-5 in fp32
+mode and <= 1e-2 in bf16 mode, per tensor (O, LSE, dQ, dK, dV)."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import dense_rollout as A
+from oracle import tree_direct as B
+from workloads import (chain_tree, config_heads, config_tree, make_inputs_numpy, random_tree,
+                       scaled_config_tree)
+from parity_util import rel_err, run_hip
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 1e-2}
+
+
+def _compare(parent, seg, Hq, Hkv, d, dtype, seed, oracle=B, scale=None):
+    T = int(np.sum(seg))
+    scale = 1.0 / math.sqrt(d) if scale is None else scale
+    inp = make_inputs_numpy(T, Hq, Hkv, d, seed, dtype=dtype)
+    got = run_hip(parent, seg, inp, Hq, Hkv, d, scale, dtype)
+    O, LSE = oracle.forward(parent, seg, inp["q"], inp["k"], inp["v"], scale)
+    dQ, dK, dV = oracle.backward(parent, seg, inp["q"], inp["k"], inp["v"], inp["do"], scale)
+    errs = {"o": rel_err(got["o"], O), "lse": rel_err(got["lse"], LSE), "dq": rel_err(got["dq"], dQ),
+            "dk": rel_err(got["dk"], dK), "dv": rel_err(got["dv"], dV)}
+    print(f"T={T} Hq={Hq} Hkv={Hkv} d={d} {dtype}: " + " ".join(f"{k}={v:.2e}" for k, v in errs.items()),
+          flush=True)
+    for name, e in errs.items():
+        assert e <= TOL[dtype], (name, e)
+    return errs
+
+
+def test_config1_fp32_exhaustive_dense_rollout_oracle():
+    parent, seg, info = config_tree(1)
+    h = config_heads(1)
+    _compare(parent, seg, h["n_q_heads"], h["n_kv_heads"], h["head_dim"], "f32", info["tensor_seed"], oracle=A)
+
+
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("Hq,Hkv", [(2, 2), (4, 1), (6, 2)])
+def test_fp32_random_forests(d, Hq, Hkv):
+    rng = np.random.default_rng(1234 + d + Hq)
+    for trial in range(3):
+        parent, seg = random_tree(rng, int(rng.integers(1, 40)), 70, n_roots=int(rng.integers(1, 4)))
+        _compare(parent, seg, Hq, Hkv, d, "f32", seed=trial)
+
+
+def test_fp32_degenerate_trees():
+    _compare(np.array([-1]), np.array([1]), 2, 1, 64, "f32", seed=1)          # one token
+    _compare(*chain_tree([1] * 9), 2, 2, 64, "f32", seed=2)                    # unary chain of 1-token nodes
+    _compare(*chain_tree([100, 37, 64]), 2, 2, 128, "f32", seed=3)             # chain = causal attention
+    _compare(np.array([-1] * 5), np.array([3, 70, 1, 64, 65]), 2, 1, 64, "f32", seed=4)   # forest of single nodes
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(4, 1), (8, 2), (2, 1), (1, 1), (3, 1), (16, 2)])
+def test_bf16_random_forests(Hq, Hkv):
+    rng = np.random.default_rng(99 + Hq)
+    for trial in range(3):
+        parent, seg = random_tree(rng, int(rng.integers(1, 40)), 90, n_roots=int(rng.integers(1, 4)))
+        _compare(parent, seg, Hq, Hkv, 128, "bf16", seed=trial)
+
+
+def test_bf16_degenerate_trees():
+    _compare(np.array([-1]), np.array([1]), 4, 1, 128, "bf16", seed=1)
+    _compare(*chain_tree([1] * 9), 4, 1, 128, "bf16", seed=2)
+    _compare(*chain_tree([300, 37, 64, 128]), 4, 2, 128, "bf16", seed=3)
+    _compare(np.array([-1] * 5), np.array([3, 70, 1, 64, 65]), 4, 1, 128, "bf16", seed=4)
+
+
+@pytest.mark.parametrize("cfg,shrink", [(2, 8), (3, 16), (4, 32), (5, 4)])
+def test_bf16_scaled_down_benchmark_configs(cfg, shrink):
+    """Siblings of the benchmark trees (same branching, shorter segments) checked
+    on whole tensors; two kv groups keep the oracle to seconds."""
+    parent, seg, info = scaled_config_tree(cfg, shrink)
+    G = config_heads(cfg)["n_q_heads"] // config_heads(cfg)["n_kv_heads"]
+    _compare(parent, seg, 2 * G, 2, 128, "bf16", seed=info["tensor_seed"])
