@@ -1,0 +1,283 @@
+#!/usr/bin/env python3
+"""Benchmark of the tree-attention hot path on one MI355X.
+
+One "step" is one pass of the whole hot path over one synthetic rollout tree:
+dta_tree_build (host metadata + tile schedule + upload) -> dta_tree_attn_fwd ->
+dta_tree_attn_bwd, with Q, K, V, dO already resident in HBM.  The reported value
+is useful TFLOP/s counting only unique (query, visible key) pairs:
+pairs * Hq * 14 * head_dim flop per step (4d forward, 10d backward).
+
+Prints ONE JSON line.  Also measured, inside the same line: per-kernel times
+(HIP events on the launch stream) and the roofline of the slowest kernel; the
+same library on the dense-expanded forest (every rollout a single chain), for
+rollout tokens/s tree vs dense; the fp64 CPU oracle on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+
+WORKLOAD_NAMES = {
+    1: "cfg1_tiny_fp32_tree",
+    2: "cfg2_grpo_single_prompt_tree",
+    3: "cfg3_multi_turn_agent_forest",
+    4: "cfg4_deep_long_context_tree",
+    5: "cfg5_large_mixed_forest",
+}
+PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+# flop per unique pair per q head, in units of head_dim, that each launch must do
+KERNEL_FLOP_D = {"fwd": 4, "dq": 6, "dkdv": 8}
+
+
+def _device_inputs(T, Hq, Hkv, d, seed, dtype):
+    import torch
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    mk = lambda h: torch.randn((T, h, d), generator=g, device="cuda", dtype=torch.float32).to(tdt)
+    return dict(q=mk(Hq), k=mk(Hkv), v=mk(Hkv), do=mk(Hq))
+
+
+class Runner:
+    """Holds device buffers for one tree shape and runs steps on them."""
+
+    def __init__(self, parent, seg, heads, seed):
+        import torch
+        import paper_2602_00482_amd as dta
+        self.dta, self.torch = dta, torch
+        self.parent, self.seg = parent, seg
+        self.T = int(np.sum(seg))
+        self.Hq, self.Hkv, self.d = heads["n_q_heads"], heads["n_kv_heads"], heads["head_dim"]
+        self.dtype = heads["dtype"]
+        self.params = dta.AttnParams(self.Hq, self.Hkv, self.d, 1.0 / math.sqrt(self.d),
+                                     dta.F32 if self.dtype == "f32" else dta.BF16)
+        x = _device_inputs(self.T, self.Hq, self.Hkv, self.d, seed, self.dtype)
+        self.q, self.k, self.v, self.do = x["q"], x["k"], x["v"], x["do"]
+        self.o = torch.empty_like(self.q)
+        self.lse = torch.empty((self.T, self.Hq), dtype=torch.float32, device="cuda")
+        self.dq = torch.empty_like(self.q)
+        self.dk = torch.empty_like(self.k)
+        self.dv = torch.empty_like(self.v)
+        self.ws = torch.empty(max(256, self.T * self.Hq * 4 + 256), dtype=torch.uint8, device="cuda")
+
+    def step(self):
+        dta = self.dta
+        tree = dta.tree_build(self.parent, self.seg)
+        tree.prepare(self.params)
+        dta.tree_attn_fwd(tree, self.params, self.q, self.k, self.v, self.o, self.lse)
+        dta.tree_attn_bwd(tree, self.params, self.q, self.k, self.v, self.o, self.lse, self.do,
+                          self.dq, self.dk, self.dv, self.ws)
+        return tree
+
+    def time_steps(self, steps, warmup):
+        torch = self.torch
+        for _ in range(warmup):
+            self.step().destroy()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            tree = self.step()
+            torch.cuda.synchronize()
+            tree.destroy()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    def time_kernels(self, iters):
+        """Average duration of each launch, HIP events on the launch stream."""
+        dta, torch = self.dta, self.torch
+        tree = dta.tree_build(self.parent, self.seg)
+        tree.prepare(self.params)
+        a = (tree, self.params, self.q, self.k, self.v, self.o, self.lse, self.do,
+             self.dq, self.dk, self.dv, self.ws)
+        launches = {
+            "fwd": lambda: dta.tree_attn_fwd(tree, self.params, self.q, self.k, self.v, self.o, self.lse),
+            "delta": lambda: dta.tree_attn_bwd(*a, stages=dta.BWD_DELTA),
+            "dq": lambda: dta.tree_attn_bwd(*a, stages=dta.BWD_DQ),
+            "dkdv": lambda: dta.tree_attn_bwd(*a, stages=dta.BWD_DKDV),
+        }
+        out = {}
+        for name, fn in launches.items():
+            fn()
+            torch.cuda.synchronize()
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(iters):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            out[name] = e0.elapsed_time(e1) / iters
+        info = tree.info()
+        sched = tree.schedule_info(self.params)
+        tree.destroy()
+        return out, info, sched
+
+
+def _dense_batches(rollout_lens, token_budget):
+    batches, cur, tot = [], [], 0
+    for n in rollout_lens:
+        if cur and tot + n > token_budget:
+            batches.append(cur)
+            cur, tot = [], 0
+        cur.append(int(n))
+        tot += int(n)
+    if cur:
+        batches.append(cur)
+    return batches
+
+
+def run_dense(rollout_lens, heads, steps, warmup, token_budget=393216):
+    """The same library on the dense-expanded forest: every rollout is its own
+    single-node tree (ordinary variable-length causal attention)."""
+    import torch
+    total = 0.0
+    shapes_done = {}
+    for batch in _dense_batches(rollout_lens, token_budget):
+        key = tuple(batch)
+        if key not in shapes_done:
+            r = Runner(np.full(len(batch), -1, dtype=np.int32), np.asarray(batch, dtype=np.int32), heads, seed=7)
+            shapes_done[key] = r.time_steps(steps, warmup)
+            del r
+            torch.cuda.empty_cache()
+        total += shapes_done[key]
+    return total
+
+
+def cpu_oracle_baseline(parent, seg, heads, seed, useful_flop):
+    """Oracle A (dense per-rollout, fp64 numpy) on one kv group of the workload,
+    timed on this machine's host cores and extrapolated linearly to all kv groups."""
+    from oracle import dense_rollout as A
+    from workloads import make_inputs_numpy
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count()
+    Hq, Hkv, d = heads["n_q_heads"], heads["n_kv_heads"], heads["head_dim"]
+    G = Hq // Hkv
+    T = int(np.sum(seg))
+    x = make_inputs_numpy(T, G, 1, d, seed, dtype=heads["dtype"])     # one kv group
+    scale = 1.0 / math.sqrt(d)
+    t0 = time.perf_counter()
+    A.forward(parent, seg, x["q"], x["k"], x["v"], scale)
+    A.backward(parent, seg, x["q"], x["k"], x["v"], x["do"], scale)
+    dt = time.perf_counter() - t0
+    full = dt * Hkv
+    return {"value": useful_flop / full / 1e12, "unit": "TFLOP/s", "cores": int(threads),
+            "kind": "oracle",
+            "sample": f"dense per-rollout fp64 oracle, fwd+bwd, 1 of {Hkv} kv groups ({G} q heads), all "
+                      f"rollouts: {dt:.1f} s measured, x{Hkv} extrapolated to {full:.0f} s for the whole job",
+            "seconds_measured": dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 2..5 of the main line")
+    ap.add_argument("--others", type=str, default="3,4,5", help="configs reported as extra objects ('' = none)")
+    ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2602_00482_amd as dta
+    from workloads import config_heads, config_tree
+    dta.load_library()          # fails loudly if the HIP library is missing
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+
+    def leaf_lengths(parent, seg):
+        tree = dta.tree_build(parent, seg)
+        lay = tree.layout()
+        tree.destroy()
+        is_leaf = np.ones(len(parent), dtype=bool)
+        is_leaf[parent[parent >= 0]] = False
+        return (lay["node_start_depth"] + seg)[is_leaf]
+
+    def measure(cfg, steps, warmup, with_dense, with_cpu):
+        parent, seg, meta = config_tree(cfg)
+        heads = config_heads(cfg)
+        r = Runner(parent, seg, heads, meta["tensor_seed"])
+        sec = r.time_steps(steps, warmup)
+        kern, info, sched = r.time_kernels(max(3, min(10, steps)))
+        Hq, d = heads["n_q_heads"], heads["head_dim"]
+        pairs = info["unique_pairs"]
+        useful = pairs * Hq * 14 * d
+        res = {
+            "workload": WORKLOAD_NAMES[cfg], "n_tokens": info["n_tokens"], "n_nodes": info["n_nodes"],
+            "n_leaves": info["n_leaves"], "max_path_tokens": info["max_path_tokens"],
+            "unique_pairs": pairs, "heads": f"{Hq}q/{heads['n_kv_heads']}kv", "head_dim": d,
+            "tree_seed": meta["tree_seed"], "tensor_seed": meta["tensor_seed"],
+            "ms_per_step": sec * 1e3, "useful_tflops": useful / sec / 1e12,
+            "mfma_frac_of_peak": useful / sec / 1e12 / PEAK_TFLOPS[heads["dtype"]],
+            "kernel_ms": {k: round(v, 4) for k, v in kern.items()},
+            "kernel_tflops": {k: pairs * Hq * KERNEL_FLOP_D[k] * d / (kern[k] * 1e-3) / 1e12
+                              for k in KERNEL_FLOP_D},
+            "schedule": sched,
+            "C_leaf": info["rollout_tokens"] / info["n_tokens"],
+            "C_full": info["rollout_tokens_full"] / info["n_tokens"],
+            "C_attn_leaf": info["dense_pairs"] / pairs,
+            "rollout_tokens_per_s_tree": info["rollout_tokens"] / sec,
+        }
+        del r
+        torch.cuda.empty_cache()
+        if with_dense:
+            dsec = run_dense(leaf_lengths(parent, seg), heads, steps=max(1, min(3, steps)), warmup=1)
+            res["ms_per_step_dense_expanded"] = dsec * 1e3
+            res["rollout_tokens_per_s_dense"] = info["rollout_tokens"] / dsec
+            res["tree_over_dense"] = dsec / sec
+        cpu = None
+        if with_cpu:
+            cpu = cpu_oracle_baseline(parent, seg, heads, meta["tensor_seed"], useful)
+        return res, kern, info, heads, cpu
+
+    main_res, kern, info, heads, cpu = measure(args.config, args.steps, args.warmup,
+                                               not args.no_dense, not args.no_cpu)
+    Hq, d = heads["n_q_heads"], heads["head_dim"]
+    dom = max(KERNEL_FLOP_D, key=lambda k: kern[k])
+    achieved = info["unique_pairs"] * Hq * KERNEL_FLOP_D[dom] * d / (kern[dom] * 1e-3) / 1e12
+    peak = PEAK_TFLOPS[heads["dtype"]]
+    line = {
+        "metric": "tree_attn_fwd_bwd_unique_pair_tflops", "value": main_res["useful_tflops"],
+        "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": main_res["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": heads["dtype"], "data": "synthetic",
+        "config": {k: main_res[k] for k in ("workload", "n_tokens", "n_nodes", "n_leaves", "max_path_tokens",
+                                            "unique_pairs", "heads", "head_dim", "tree_seed", "tensor_seed")},
+        "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+                     "frac": achieved / peak, "traffic": None,
+                     "flop_per_pair_per_head": KERNEL_FLOP_D[dom] * d, "avg_launch_ms": kern[dom]},
+        "cpu_baseline": cpu,
+        "detail": main_res,
+    }
+    others = {}
+    for c in [int(x) for x in args.others.split(",") if x.strip()]:
+        if c == args.config:
+            continue
+        res, *_ = measure(c, max(2, min(5, args.steps)), 1, not args.no_dense, False)
+        others[WORKLOAD_NAMES[c]] = res
+    if others:
+        line["other_configs"] = others
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

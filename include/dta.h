@@ -174,6 +174,20 @@ int dta_tree_attn_bwd(dta_tree_t* tree, const dta_attn_params_t* params, const v
                       const void* d_o, void* dq, void* dk, void* dv, void* workspace,
                       size_t workspace_bytes, void* hip_stream);
 
+/*
+ * dta_tree_attn_bwd_stages - the same backward pass, restricted to the stages in
+ * stage_mask, for callers that need only some gradients or that time the
+ * launches one by one.  dta_tree_attn_bwd equals DTA_BWD_ALL.  DTA_BWD_DQ and
+ * DTA_BWD_DKDV read the D values DTA_BWD_DELTA leaves in the workspace, so the
+ * delta stage must have run on the same workspace, o and d_o before them.
+ * Outputs of stages that are not selected are not touched (and may be NULL).
+ */
+enum { DTA_BWD_DELTA = 1, DTA_BWD_DQ = 2, DTA_BWD_DKDV = 4, DTA_BWD_ALL = 7 };
+int dta_tree_attn_bwd_stages(dta_tree_t* tree, const dta_attn_params_t* params, const void* q,
+                             const void* k, const void* v, const void* o, const float* lse,
+                             const void* d_o, void* dq, void* dk, void* dv, void* workspace,
+                             size_t workspace_bytes, void* hip_stream, uint32_t stage_mask);
+
 /* Static, human-readable name of a status code. */
 const char* dta_status_string(int status);
 

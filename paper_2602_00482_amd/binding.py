@@ -19,7 +19,7 @@ F32, BF16 = 0, 1
 exported_symbols = [
     "dta_tree_build", "dta_tree_info", "dta_tree_layout", "dta_tree_schedule_info",
     "dta_tree_destroy", "dta_tree_attn_workspace_bytes", "dta_tree_attn_prepare",
-    "dta_tree_attn_fwd", "dta_tree_attn_bwd", "dta_status_string",
+    "dta_tree_attn_fwd", "dta_tree_attn_bwd", "dta_tree_attn_bwd_stages", "dta_status_string",
 ]
 
 
@@ -82,6 +82,8 @@ def load_library():
     lib.dta_tree_attn_fwd.restype = C.c_int
     lib.dta_tree_attn_bwd.argtypes = [vp, C.POINTER(AttnParams)] + [vp] * 9 + [vp, C.c_size_t, vp]
     lib.dta_tree_attn_bwd.restype = C.c_int
+    lib.dta_tree_attn_bwd_stages.argtypes = [vp, C.POINTER(AttnParams)] + [vp] * 9 + [vp, C.c_size_t, vp, C.c_uint32]
+    lib.dta_tree_attn_bwd_stages.restype = C.c_int
     lib.dta_status_string.argtypes = [C.c_int]
     lib.dta_status_string.restype = C.c_char_p
     _lib = lib
@@ -200,9 +202,13 @@ def tree_attn_fwd(tree: Tree, params: AttnParams, q, k, v, o=None, lse=None, wor
     return o, lse
 
 
+BWD_DELTA, BWD_DQ, BWD_DKDV, BWD_ALL = 1, 2, 4, 7
+
+
 def tree_attn_bwd(tree: Tree, params: AttnParams, q, k, v, o, lse, d_o, dq=None, dk=None, dv=None,
-                  workspace=None):
-    """dta_tree_attn_bwd on torch's current stream.  Returns (dq, dk, dv)."""
+                  workspace=None, stages: int = BWD_ALL):
+    """dta_tree_attn_bwd (or dta_tree_attn_bwd_stages when `stages` selects a
+    subset) on torch's current stream.  Returns (dq, dk, dv)."""
     import torch
     dt = torch.float32 if params.dtype == F32 else torch.bfloat16
     T = q.shape[0]
@@ -222,8 +228,11 @@ def tree_attn_bwd(tree: Tree, params: AttnParams, q, k, v, o, lse, d_o, dq=None,
         need = workspace_bytes(tree, params, True)
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
     ws_bytes = workspace.numel() * workspace.element_size()
-    st = load_library().dta_tree_attn_bwd(tree.handle, C.byref(params), _ptr(q), _ptr(k), _ptr(v),
-                                          _ptr(o), _ptr(lse), _ptr(d_o), _ptr(dq), _ptr(dk), _ptr(dv),
-                                          _ptr(workspace), ws_bytes, _stream())
-    _check(st, "dta_tree_attn_bwd")
+    lib = load_library()
+    args = (tree.handle, C.byref(params), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o),
+            _ptr(dq), _ptr(dk), _ptr(dv), _ptr(workspace), ws_bytes, _stream())
+    if stages == BWD_ALL:
+        _check(lib.dta_tree_attn_bwd(*args), "dta_tree_attn_bwd")
+    else:
+        _check(lib.dta_tree_attn_bwd_stages(*args, int(stages)), "dta_tree_attn_bwd_stages")
     return dq, dk, dv

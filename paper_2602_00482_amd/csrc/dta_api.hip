@@ -2,6 +2,7 @@
 // dispatch to the kernel launchers.  See include/dta.h for the contract.
 #include <hip/hip_runtime.h>
 
+#include <cstdio>
 #include <new>
 
 #include "dta_internal.h"
@@ -24,11 +25,17 @@ int upload(const std::vector<T>& host, T** dev) {
   if (bytes == 0) bytes = sizeof(T);
   if (hipMalloc((void**)dev, bytes) != hipSuccess) {
     *dev = nullptr;
+    (void)hipGetLastError();
     return DTA_ERR_ALLOC;
   }
-  if (!host.empty() &&
-      hipMemcpy(*dev, host.data(), host.size() * sizeof(T), hipMemcpyHostToDevice) != hipSuccess)
-    return DTA_ERR_HIP;
+  if (!host.empty()) {
+    hipError_t e = hipMemcpy(*dev, host.data(), host.size() * sizeof(T), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+      fprintf(stderr, "dta: metadata upload: %s\n", hipGetErrorString(e));
+      (void)hipGetLastError();
+      return DTA_ERR_HIP;
+    }
+  }
   return DTA_OK;
 }
 
@@ -37,7 +44,11 @@ int upload(const std::vector<T>& host, T** dev) {
 int ensure_device(dta_tree* tree, const dta::TileChoice& tc, dta::Schedule** out) {
   std::lock_guard<std::mutex> lock(tree->mu);
   int dev = -1;
-  if (hipGetDevice(&dev) != hipSuccess) return DTA_ERR_HIP;
+  if (hipGetDevice(&dev) != hipSuccess) {
+    fprintf(stderr, "dta: hipGetDevice failed (no usable GPU?)\n");
+    (void)hipGetLastError();
+    return DTA_ERR_HIP;
+  }
   dta::Schedule* s;
   try {
     s = &dta::get_schedule(tree, tc.bm, tc.bn);
@@ -62,6 +73,19 @@ int ensure_device(dta_tree* tree, const dta::TileChoice& tc, dta::Schedule** out
 inline bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
 
 }  // namespace
+
+namespace dta {
+
+void clear_hip_error() { (void)hipGetLastError(); }
+
+int launch_status(const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess) return DTA_OK;
+  fprintf(stderr, "dta: %s: %s\n", what, hipGetErrorString(e));
+  return DTA_ERR_HIP;
+}
+
+}  // namespace dta
 
 extern "C" {
 
@@ -121,15 +145,18 @@ int dta_tree_attn_fwd(dta_tree_t* tree, const dta_attn_params_t* params, const v
   return params->dtype == DTA_F32 ? dta::launch_fwd_f32(a) : dta::launch_fwd_bf16(a);
 }
 
-int dta_tree_attn_bwd(dta_tree_t* tree, const dta_attn_params_t* params, const void* q,
-                      const void* k, const void* v, const void* o, const float* lse,
-                      const void* d_o, void* dq, void* dk, void* dv, void* workspace,
-                      size_t workspace_bytes, void* hip_stream) {
+int dta_tree_attn_bwd_stages(dta_tree_t* tree, const dta_attn_params_t* params, const void* q,
+                             const void* k, const void* v, const void* o, const float* lse,
+                             const void* d_o, void* dq, void* dk, void* dv, void* workspace,
+                             size_t workspace_bytes, void* hip_stream, uint32_t stage_mask) {
   if (!tree || !params) return DTA_ERR_INVALID_ARG;
+  if (stage_mask == 0 || (stage_mask & ~(uint32_t)DTA_BWD_ALL)) return DTA_ERR_INVALID_ARG;
   dta::TileChoice tc;
   int st = dta::choose_tiles(params, &tc);
   if (st != DTA_OK) return st;
-  if (!q || !k || !v || !o || !lse || !d_o || !dq || !dk || !dv) return DTA_ERR_INVALID_ARG;
+  const bool want_dq = stage_mask & DTA_BWD_DQ, want_dkdv = stage_mask & DTA_BWD_DKDV;
+  if (!q || !k || !v || !o || !lse || !d_o) return DTA_ERR_INVALID_ARG;
+  if ((want_dq && !dq) || (want_dkdv && (!dk || !dv))) return DTA_ERR_INVALID_ARG;
   if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse) ||
       misaligned(d_o) || misaligned(dq) || misaligned(dk) || misaligned(dv))
     return DTA_ERR_INVALID_ARG;
@@ -153,8 +180,17 @@ int dta_tree_attn_bwd(dta_tree_t* tree, const dta_attn_params_t* params, const v
   a.dk = dk;
   a.dv = dv;
   a.delta = (float*)workspace;
+  a.stages = stage_mask;
   a.stream = hip_stream;
   return params->dtype == DTA_F32 ? dta::launch_bwd_f32(a) : dta::launch_bwd_bf16(a);
+}
+
+int dta_tree_attn_bwd(dta_tree_t* tree, const dta_attn_params_t* params, const void* q,
+                      const void* k, const void* v, const void* o, const float* lse,
+                      const void* d_o, void* dq, void* dk, void* dv, void* workspace,
+                      size_t workspace_bytes, void* hip_stream) {
+  return dta_tree_attn_bwd_stages(tree, params, q, k, v, o, lse, d_o, dq, dk, dv, workspace,
+                                  workspace_bytes, hip_stream, DTA_BWD_ALL);
 }
 
 }  // extern "C"

@@ -346,24 +346,31 @@ __global__ __launch_bounds__(256) void dkdv_bf16_kernel(
 
 int launch_bwd_bf16(const LaunchArgs& a) {
   hipStream_t st = (hipStream_t)a.stream;
+  clear_hip_error();
   const size_t rows = (size_t)a.tree->info.n_tokens * a.p.n_q_heads;
-  delta_bf16_kernel<<<(unsigned)((rows + 15) / 16), 256, 0, st>>>(
-      (const uint16_t*)a.o, (const uint16_t*)a.d_o, a.delta, rows);
-  if (hipGetLastError() != hipSuccess) return DTA_ERR_HIP;
-
   const size_t qblocks = a.sched->q_tiles.size() * (size_t)a.p.n_kv_heads * (size_t)a.tc.hblocks;
   const size_t kblocks = a.sched->kv_tiles.size() * (size_t)a.p.n_kv_heads;
   if (qblocks == 0 || qblocks > 0x7fffffffu || kblocks > 0x7fffffffu) return DTA_ERR_UNSUPPORTED;
-  dq_bf16_kernel<<<(unsigned)qblocks, 256, 0, st>>>(
-      a.sched->d_q_tiles, a.sched->d_segs, a.d_kend, (const uint16_t*)a.q, (const uint16_t*)a.k,
-      (const uint16_t*)a.v, (const uint16_t*)a.d_o, a.lse_in, a.delta, (uint16_t*)a.dq,
-      a.p.n_q_heads, a.p.n_kv_heads, a.tc.hb, a.tc.hblocks, a.p.softmax_scale);
-  if (hipGetLastError() != hipSuccess) return DTA_ERR_HIP;
-  dkdv_bf16_kernel<<<(unsigned)kblocks, 256, 0, st>>>(
-      a.sched->d_kv_tiles, a.d_kend, (const uint16_t*)a.q, (const uint16_t*)a.k,
-      (const uint16_t*)a.v, (const uint16_t*)a.d_o, a.lse_in, a.delta, (uint16_t*)a.dk,
-      (uint16_t*)a.dv, a.p.n_q_heads, a.p.n_kv_heads, a.p.softmax_scale);
-  return hipGetLastError() == hipSuccess ? DTA_OK : DTA_ERR_HIP;
+  if (a.stages & DTA_BWD_DELTA) {
+    delta_bf16_kernel<<<(unsigned)((rows + 15) / 16), 256, 0, st>>>(
+        (const uint16_t*)a.o, (const uint16_t*)a.d_o, a.delta, rows);
+    { int ls = launch_status(__func__); if (ls != DTA_OK) return ls; }
+  }
+  if (a.stages & DTA_BWD_DQ) {
+    dq_bf16_kernel<<<(unsigned)qblocks, 256, 0, st>>>(
+        a.sched->d_q_tiles, a.sched->d_segs, a.d_kend, (const uint16_t*)a.q, (const uint16_t*)a.k,
+        (const uint16_t*)a.v, (const uint16_t*)a.d_o, a.lse_in, a.delta, (uint16_t*)a.dq,
+        a.p.n_q_heads, a.p.n_kv_heads, a.tc.hb, a.tc.hblocks, a.p.softmax_scale);
+    { int ls = launch_status(__func__); if (ls != DTA_OK) return ls; }
+  }
+  if (a.stages & DTA_BWD_DKDV) {
+    dkdv_bf16_kernel<<<(unsigned)kblocks, 256, 0, st>>>(
+        a.sched->d_kv_tiles, a.d_kend, (const uint16_t*)a.q, (const uint16_t*)a.k,
+        (const uint16_t*)a.v, (const uint16_t*)a.d_o, a.lse_in, a.delta, (uint16_t*)a.dk,
+        (uint16_t*)a.dv, a.p.n_q_heads, a.p.n_kv_heads, a.p.softmax_scale);
+    { int ls = launch_status(__func__); if (ls != DTA_OK) return ls; }
+  }
+  return DTA_OK;
 }
 
 }  // namespace dta

@@ -223,13 +223,14 @@ __global__ __launch_bounds__(256) void fwd_bf16_kernel(
 
 int launch_fwd_bf16(const LaunchArgs& a) {
   hipStream_t st = (hipStream_t)a.stream;
+  clear_hip_error();
   const size_t blocks = a.sched->q_tiles.size() * (size_t)a.p.n_kv_heads * (size_t)a.tc.hblocks;
   if (blocks == 0 || blocks > 0x7fffffffu) return DTA_ERR_UNSUPPORTED;
   fwd_bf16_kernel<<<(unsigned)blocks, 256, 0, st>>>(
       a.sched->d_q_tiles, a.sched->d_segs, a.d_kend, (const uint16_t*)a.q, (const uint16_t*)a.k,
       (const uint16_t*)a.v, (uint16_t*)a.o_out, a.lse_out, a.p.n_q_heads, a.p.n_kv_heads, a.tc.hb,
       a.tc.hblocks, a.p.softmax_scale);
-  return hipGetLastError() == hipSuccess ? DTA_OK : DTA_ERR_HIP;
+  return launch_status(__func__);
 }
 
 }  // namespace dta

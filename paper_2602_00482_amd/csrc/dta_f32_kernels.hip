@@ -264,34 +264,43 @@ __global__ __launch_bounds__(256) void dkdv_f32_kernel(const KvTile* __restrict_
 template <int D>
 int fwd_impl(const LaunchArgs& a) {
   hipStream_t st = (hipStream_t)a.stream;
+  clear_hip_error();
   dim3 grid((unsigned)a.sched->q_tiles.size(), (unsigned)a.p.n_q_heads);
   fwd_f32_kernel<D><<<grid, 256, 0, st>>>(a.sched->d_q_tiles, a.sched->d_segs, a.d_kend,
                                           (const float*)a.q, (const float*)a.k, (const float*)a.v,
                                           (float*)a.o_out, a.lse_out, a.p.n_q_heads, a.p.n_kv_heads,
                                           a.p.softmax_scale);
-  return hipGetLastError() == hipSuccess ? DTA_OK : DTA_ERR_HIP;
+  return launch_status(__func__);
 }
 
 template <int D>
 int bwd_impl(const LaunchArgs& a) {
   hipStream_t st = (hipStream_t)a.stream;
+  clear_hip_error();
   const size_t rows = (size_t)a.tree->info.n_tokens * a.p.n_q_heads;
-  delta_f32_kernel<D><<<(unsigned)((rows + kRows - 1) / kRows), 256, 0, st>>>(
-      (const float*)a.o, (const float*)a.d_o, a.delta, rows);
-  if (hipGetLastError() != hipSuccess) return DTA_ERR_HIP;
-  dim3 gq((unsigned)a.sched->q_tiles.size(), (unsigned)a.p.n_q_heads);
-  dq_f32_kernel<D><<<gq, 256, 0, st>>>(a.sched->d_q_tiles, a.sched->d_segs, a.d_kend,
-                                       (const float*)a.q, (const float*)a.k, (const float*)a.v,
-                                       (const float*)a.d_o, a.lse_in, a.delta, (float*)a.dq,
-                                       a.p.n_q_heads, a.p.n_kv_heads, a.p.softmax_scale);
-  if (hipGetLastError() != hipSuccess) return DTA_ERR_HIP;
-  dim3 gk((unsigned)a.sched->kv_tiles.size(), (unsigned)a.p.n_kv_heads);
-  dkdv_f32_kernel<D><<<gk, 256, 0, st>>>(a.sched->d_kv_tiles, a.d_kend, (const float*)a.q,
-                                         (const float*)a.k, (const float*)a.v,
-                                         (const float*)a.d_o, a.lse_in, a.delta, (float*)a.dk,
-                                         (float*)a.dv, a.p.n_q_heads, a.p.n_kv_heads,
-                                         a.p.softmax_scale);
-  return hipGetLastError() == hipSuccess ? DTA_OK : DTA_ERR_HIP;
+  if (a.stages & DTA_BWD_DELTA) {
+    delta_f32_kernel<D><<<(unsigned)((rows + kRows - 1) / kRows), 256, 0, st>>>(
+        (const float*)a.o, (const float*)a.d_o, a.delta, rows);
+    { int ls = launch_status(__func__); if (ls != DTA_OK) return ls; }
+  }
+  if (a.stages & DTA_BWD_DQ) {
+    dim3 gq((unsigned)a.sched->q_tiles.size(), (unsigned)a.p.n_q_heads);
+    dq_f32_kernel<D><<<gq, 256, 0, st>>>(a.sched->d_q_tiles, a.sched->d_segs, a.d_kend,
+                                         (const float*)a.q, (const float*)a.k, (const float*)a.v,
+                                         (const float*)a.d_o, a.lse_in, a.delta, (float*)a.dq,
+                                         a.p.n_q_heads, a.p.n_kv_heads, a.p.softmax_scale);
+    { int ls = launch_status(__func__); if (ls != DTA_OK) return ls; }
+  }
+  if (a.stages & DTA_BWD_DKDV) {
+    dim3 gk((unsigned)a.sched->kv_tiles.size(), (unsigned)a.p.n_kv_heads);
+    dkdv_f32_kernel<D><<<gk, 256, 0, st>>>(a.sched->d_kv_tiles, a.d_kend, (const float*)a.q,
+                                           (const float*)a.k, (const float*)a.v,
+                                           (const float*)a.d_o, a.lse_in, a.delta, (float*)a.dk,
+                                           (float*)a.dv, a.p.n_q_heads, a.p.n_kv_heads,
+                                           a.p.softmax_scale);
+    { int ls = launch_status(__func__); if (ls != DTA_OK) return ls; }
+  }
+  return DTA_OK;
 }
 
 }  // namespace

@@ -98,8 +98,16 @@ struct LaunchArgs {
   void *o_out, *dq, *dk, *dv;
   float* lse_out;
   float* delta;  // workspace: D[t,h] = dO.O
+  uint32_t stages;  // backward stages to launch (DTA_BWD_*)
   void* stream;
 };
+
+// HIP keeps the last error of earlier, unrelated runtime calls of this thread
+// (the caller's framework may have left one behind).  clear_hip_error() drops it
+// before a launch; launch_status() turns the launch's own result into a DTA
+// status and names a failure on stderr.
+void clear_hip_error();
+int launch_status(const char* what);
 
 // Kernel launchers (defined in the .hip files); return a DTA status.
 int launch_fwd_f32(const LaunchArgs& a);
