@@ -18,11 +18,11 @@
 
 #include "dta_internal.h"
 #include "dta_mfma.h"
+#include "dta_tile_walk.h"
 
 namespace dta {
 namespace {
 
-constexpr int kBN = 64;   // keys per streamed tile in the dQ kernel
 constexpr int kBQ = 64;   // query rows per streamed tile in the dK/dV kernel
 
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) {
@@ -53,40 +53,20 @@ __global__ __launch_bounds__(256) void delta_bf16_kernel(const uint16_t* __restr
   if (row < rows && j == 0) delta[row] = s;
 }
 
-struct KeyChunks {
-  const KeySeg* segs;
-  int si, seg_end, t0, t1;
-  int cur, end, full;
-  __device__ __forceinline__ void load_seg() {
-    if (si < seg_end) {
-      cur = segs[si].start; end = segs[si].end; full = segs[si].full;
-    } else {
-      cur = t0; end = t1; full = 0;
-    }
-  }
-  __device__ __forceinline__ void init(const KeySeg* s, const QTile& t) {
-    segs = s; si = t.seg_begin; seg_end = t.seg_end; t0 = t.t0; t1 = t.t1;
-    load_seg();
-  }
-  __device__ __forceinline__ bool next(int& c0, int& n, int& is_full) {
-    if (si > seg_end) return false;
-    c0 = cur; n = min(kBN, end - cur); is_full = full;
-    cur += kBN;
-    if (cur >= end) { ++si; if (si <= seg_end) load_seg(); }
-    return true;
-  }
-};
+constexpr int kDqThreads = 512;
 
-__global__ __launch_bounds__(256) void dq_bf16_kernel(
+// Query-stationary dQ: 8 waves, each 32 query rows of one q head (same walk and
+// wave layout as the forward kernel).
+__global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
     const QTile* __restrict__ tiles, const KeySeg* __restrict__ segs,
     const int32_t* __restrict__ kend, const uint16_t* __restrict__ q,
     const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const uint16_t* __restrict__ d_o, const float* __restrict__ lse,
     const float* __restrict__ delta, uint16_t* __restrict__ dq, int Hq, int Hkv, int HB,
     int hblocks, float scale) {
-  __shared__ __attribute__((aligned(16))) uint16_t Ks[kBN * kPitch];
-  __shared__ __attribute__((aligned(16))) uint16_t Vs[kBN * kPitch];
-  __shared__ int32_t kendS[kBN];
+  __shared__ __attribute__((aligned(16))) uint16_t Ks[kKeyChunk * kPitchBoth];
+  __shared__ __attribute__((aligned(16))) uint16_t Vs[kKeyChunk * kPitchRow];
+  __shared__ int32_t kendS[kKeyChunk];
 
   const int inner = blockIdx.x % (Hkv * hblocks);
   const QTile tile = tiles[blockIdx.x / (Hkv * hblocks)];
@@ -95,34 +75,28 @@ __global__ __launch_bounds__(256) void dq_bf16_kernel(
   const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
   const int c = l & 31, hh = l >> 5;
   const int h = g * G + hblk * HB + (w % HB);
-  const int row_base = tile.t0 + 64 * (w / HB);
+  const int row_base = tile.t0 + 32 * (w / HB);
   const float sc = scale * kLog2e;
 
-  int qrow[2];
-  float lse2[2], dlt[2];
-  bf16x8 Qr[2][8], dOr[2][8];
-#pragma unroll
-  for (int nb = 0; nb < 2; ++nb) {
-    qrow[nb] = min(row_base + 32 * nb + c, tile.t1 - 1);
-    const size_t rh = (size_t)qrow[nb] * Hq + h;
+  const int qrow = min(row_base + c, tile.t1 - 1);
+  const size_t rh = (size_t)qrow * Hq + h;
+  bf16x8 Qr[8], dOr[8];
+  {
     const uint16_t* qp = q + rh * kHeadDim + 8 * hh;
     const uint16_t* dop = d_o + rh * kHeadDim + 8 * hh;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-      Qr[nb][ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
-      dOr[nb][ks] = *reinterpret_cast<const bf16x8*>(dop + 16 * ks);
+      Qr[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
+      dOr[ks] = *reinterpret_cast<const bf16x8*>(dop + 16 * ks);
     }
-    lse2[nb] = lse[rh] * kLog2e;
-    dlt[nb] = delta[rh];
   }
+  const float lse2 = lse[rh] * kLog2e, dlt = delta[rh];
 
-  f32x16 dQ[4][2];
+  f32x16 dQ[4];
 #pragma unroll
   for (int a = 0; a < 4; ++a)
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) dQ[a][b][e] = 0.f;
+    for (int e = 0; e < 16; ++e) dQ[a][e] = 0.f;
 
   const size_t kv_stride = (size_t)Hkv * kHeadDim;
   const uint16_t* kbase = k + (size_t)g * kHeadDim;
@@ -132,15 +106,16 @@ __global__ __launch_bounds__(256) void dq_bf16_kernel(
   it.init(segs, tile);
   int c0, n, full;
   bool have = it.next(c0, n, full);
-  TileRegs kreg, vreg;
+  TileRegs<kDqThreads> kreg, vreg;
   tile_load(kreg, kbase + (size_t)c0 * kv_stride, kv_stride, n);
   tile_load(vreg, vbase + (size_t)c0 * kv_stride, kv_stride, n);
 
   while (have) {
     __syncthreads();
-    tile_store(kreg, Ks);
-    tile_store(vreg, Vs);
-    if (!full && threadIdx.x < kBN) kendS[threadIdx.x] = threadIdx.x < n ? kend[c0 + threadIdx.x] : 0;
+    tile_store<kPitchBoth>(kreg, Ks);
+    tile_store<kPitchRow>(vreg, Vs);
+    if (!full && threadIdx.x < kKeyChunk)
+      kendS[threadIdx.x] = (int)threadIdx.x < n ? kend[c0 + threadIdx.x] : 0;
     __syncthreads();
     const int cc0 = c0, cn = n, cfull = full;
     have = it.next(c0, n, full);
@@ -148,80 +123,73 @@ __global__ __launch_bounds__(256) void dq_bf16_kernel(
       tile_load(kreg, kbase + (size_t)c0 * kv_stride, kv_stride, n);
       tile_load(vreg, vbase + (size_t)c0 * kv_stride, kv_stride, n);
     }
-    const bool need_mask = !cfull || cn < kBN;
+    const bool need_mask = !cfull || cn < kKeyChunk;
 
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb) {
-      f32x16 S[2], dP[2];
+      f32x16 S, dP;
 #pragma unroll
-      for (int b = 0; b < 2; ++b)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) { S[b][e] = 0.f; dP[b][e] = 0.f; }
+      for (int e = 0; e < 16; ++e) { S[e] = 0.f; dP[e] = 0.f; }
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 ka = lds_read_row8(Ks + (32 * mb + c) * kPitch + 16 * ks + 8 * hh);
-        const bf16x8 va = lds_read_row8(Vs + (32 * mb + c) * kPitch + 16 * ks + 8 * hh);
-        S[0] = mfma32(ka, Qr[0][ks], S[0]);
-        S[1] = mfma32(ka, Qr[1][ks], S[1]);
-        dP[0] = mfma32(va, dOr[0][ks], dP[0]);
-        dP[1] = mfma32(va, dOr[1][ks], dP[1]);
+        const bf16x8 ka = lds_read_row8(Ks + (32 * mb + c) * kPitchBoth + 16 * ks + 8 * hh);
+        const bf16x8 va = lds_read_row8(Vs + (32 * mb + c) * kPitchRow + 16 * ks + 8 * hh);
+        S = mfma32(ka, Qr[ks], S);
+        dP = mfma32(va, dOr[ks], dP);
       }
-      bf16x8 dSb[2][2];
 #pragma unroll
-      for (int nb = 0; nb < 2; ++nb) {
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          float p = __builtin_amdgcn_exp2f(S[nb][e] * sc - lse2[nb]);
-          if (need_mask) {
-            const int kvl = 32 * mb + 8 * (e / 4) + 4 * hh + (e % 4);
-            const int ke = cfull ? 0x7fffffff : kendS[kvl];
-            const bool ok = kvl < cn && (cfull || cc0 + kvl <= qrow[nb]) && qrow[nb] < ke;
-            if (!ok) p = 0.f;
-          }
-          S[nb][e] = p * (dP[nb][e] - dlt[nb]);
+      for (int e = 0; e < 16; ++e) {
+        float p = __builtin_amdgcn_exp2f(fmaf(S[e], sc, -lse2));
+        if (need_mask) {
+          const int kvl = 32 * mb + 8 * (e / 4) + 4 * hh + (e % 4);
+          const int ke = cfull ? 0x7fffffff : kendS[kvl];
+          const bool ok = kvl < cn && (cfull || cc0 + kvl <= qrow) && qrow < ke;
+          if (!ok) p = 0.f;
         }
-        dSb[nb][0] = pack8(S[nb], 0);
-        dSb[nb][1] = pack8(S[nb], 1);
+        S[e] = p * (dP[e] - dlt);
       }
+      const bf16x8 dSb0 = pack8(S, 0), dSb1 = pack8(S, 1);
       // dQ^T += K^T dS^T over this 32-key half
 #pragma unroll
-      for (int s = 0; s < 2; ++s)
-#pragma unroll
-        for (int dmb = 0; dmb < 4; ++dmb) {
-          const bf16x8 kt = lds_read_col8(Ks, 32 * mb + 16 * s, 32 * dmb);
-          dQ[dmb][0] = mfma32(kt, dSb[0][s], dQ[dmb][0]);
-          dQ[dmb][1] = mfma32(kt, dSb[1][s], dQ[dmb][1]);
-        }
+      for (int dmb = 0; dmb < 4; ++dmb) {
+        const bf16x8 kt0 = lds_read_col8<kPitchBoth>(Ks, 32 * mb, 32 * dmb);
+        const bf16x8 kt1 = lds_read_col8<kPitchBoth>(Ks, 32 * mb + 16, 32 * dmb);
+        dQ[dmb] = mfma32(kt0, dSb0, dQ[dmb]);
+        dQ[dmb] = mfma32(kt1, dSb1, dQ[dmb]);
+      }
     }
   }
 
+  const int token = row_base + c;
+  if (token < tile.t1) {
+    uint16_t* op = dq + ((size_t)token * Hq + h) * kHeadDim + 4 * hh;
 #pragma unroll
-  for (int nb = 0; nb < 2; ++nb) {
-    const int token = row_base + 32 * nb + c;
-    if (token < tile.t1) {
-      uint16_t* op = dq + ((size_t)token * Hq + h) * kHeadDim + 4 * hh;
+    for (int dmb = 0; dmb < 4; ++dmb)
 #pragma unroll
-      for (int dmb = 0; dmb < 4; ++dmb)
+      for (int v4 = 0; v4 < 4; ++v4) {
+        bf16x4 r;
 #pragma unroll
-        for (int v4 = 0; v4 < 4; ++v4) {
-          bf16x4 r;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) r[e] = (__bf16)(dQ[dmb][nb][4 * v4 + e] * scale);
-          *reinterpret_cast<bf16x4*>(op + 32 * dmb + 8 * v4) = r;
-        }
-    }
+        for (int e = 0; e < 4; ++e) r[e] = (__bf16)(dQ[dmb][4 * v4 + e] * scale);
+        *reinterpret_cast<bf16x4*>(op + 32 * dmb + 8 * v4) = r;
+      }
   }
 }
 
-__global__ __launch_bounds__(256) void dkdv_bf16_kernel(
+constexpr int kKvThreads = 256;
+
+// Key-stationary dK/dV: 4 waves, 32 key columns each, K and V rows in
+// registers.  Two blocks share a CU (everything fits in 256 registers), so one
+// block's global loads and barriers are covered by the other's matrix work.
+__global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
     const KvTile* __restrict__ tiles, const int32_t* __restrict__ kend,
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, const uint16_t* __restrict__ d_o,
     const float* __restrict__ lse, const float* __restrict__ delta, uint16_t* __restrict__ dk,
     uint16_t* __restrict__ dv, int Hq, int Hkv, float scale) {
-  __shared__ __attribute__((aligned(16))) uint16_t Qs[kBQ * kPitch];
-  __shared__ __attribute__((aligned(16))) uint16_t dOs[kBQ * kPitch];
-  __shared__ float lseS[kBQ], dltS[kBQ];
+  __shared__ __attribute__((aligned(16))) uint16_t Qs[kBQ * kPitchBoth];
+  __shared__ __attribute__((aligned(16))) uint16_t dOs[kBQ * kPitchBoth];
+  __shared__ __attribute__((aligned(16))) float lseS[kBQ];
+  __shared__ __attribute__((aligned(16))) float dltS[kBQ];
 
   const KvTile tile = tiles[blockIdx.x / Hkv];
   const int g = blockIdx.x % Hkv;
@@ -254,33 +222,27 @@ __global__ __launch_bounds__(256) void dkdv_bf16_kernel(
   // flat iteration over (head of the group, 64-row query chunk)
   const int n_chunks = (tile.q_end - tile.k0 + kBQ - 1) / kBQ;
   const int total = n_chunks * G;
-  TileRegs qreg, doreg;
-  float lse_r = 0.f, dlt_r = 0.f;
-  auto issue = [&](int it) {
-    const int hsub = it / n_chunks, ch = it % n_chunks;
+
+  for (int it = 0; it < total; ++it) {
+    const int hsub = it / n_chunks, ch = it - hsub * n_chunks;
     const int h = g * G + hsub;
     const int r0 = tile.k0 + ch * kBQ;
     const int nv = min(kBQ, tile.q_end - r0);
-    tile_load(qreg, q + (size_t)r0 * q_stride + (size_t)h * kHeadDim, q_stride, nv);
-    tile_load(doreg, d_o + (size_t)r0 * q_stride + (size_t)h * kHeadDim, q_stride, nv);
-    if (threadIdx.x < kBQ) {
-      const bool okr = (int)threadIdx.x < nv;
-      lse_r = okr ? lse[(size_t)(r0 + threadIdx.x) * Hq + h] * kLog2e : 0.f;
-      dlt_r = okr ? delta[(size_t)(r0 + threadIdx.x) * Hq + h] : 0.f;
+    {
+      TileRegs<kKvThreads> qreg, doreg;
+      tile_load(qreg, q + (size_t)r0 * q_stride + (size_t)h * kHeadDim, q_stride, nv);
+      tile_load(doreg, d_o + (size_t)r0 * q_stride + (size_t)h * kHeadDim, q_stride, nv);
+      float lse_r = 0.f, dlt_r = 0.f;
+      if (threadIdx.x < kBQ && (int)threadIdx.x < nv) {
+        lse_r = lse[(size_t)(r0 + threadIdx.x) * Hq + h] * kLog2e;
+        dlt_r = delta[(size_t)(r0 + threadIdx.x) * Hq + h];
+      }
+      __syncthreads();   // every wave is done reading the previous chunk
+      tile_store<kPitchBoth>(qreg, Qs);
+      tile_store<kPitchBoth>(doreg, dOs);
+      if (threadIdx.x < kBQ) { lseS[threadIdx.x] = lse_r; dltS[threadIdx.x] = dlt_r; }
+      __syncthreads();
     }
-  };
-  if (total > 0) issue(0);
-
-  for (int it = 0; it < total; ++it) {
-    __syncthreads();
-    tile_store(qreg, Qs);
-    tile_store(doreg, dOs);
-    if (threadIdx.x < kBQ) { lseS[threadIdx.x] = lse_r; dltS[threadIdx.x] = dlt_r; }
-    __syncthreads();
-    const int ch = it % n_chunks;
-    const int r0 = tile.k0 + ch * kBQ;
-    const int nv = min(kBQ, tile.q_end - r0);
-    if (it + 1 < total) issue(it + 1);
     const bool need_mask = !(r0 >= tile.k1 && r0 + kBQ <= tile.q_full_end);
 
 #pragma unroll
@@ -290,34 +252,43 @@ __global__ __launch_bounds__(256) void dkdv_bf16_kernel(
       for (int e = 0; e < 16; ++e) { S[e] = 0.f; dP[e] = 0.f; }
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 qa = lds_read_row8(Qs + (32 * mq + c) * kPitch + 16 * ks + 8 * hh);
-        const bf16x8 da = lds_read_row8(dOs + (32 * mq + c) * kPitch + 16 * ks + 8 * hh);
+        const bf16x8 qa = lds_read_row8(Qs + (32 * mq + c) * kPitchBoth + 16 * ks + 8 * hh);
+        const bf16x8 da = lds_read_row8(dOs + (32 * mq + c) * kPitchBoth + 16 * ks + 8 * hh);
         S = mfma32(qa, Kr[ks], S);
         dP = mfma32(da, Vr[ks], dP);
       }
-      f32x16 dS;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int rl = 32 * mq + 8 * (e / 4) + 4 * hh + (e % 4);
-        float p = __builtin_amdgcn_exp2f(S[e] * sc - lseS[rl]);
-        if (need_mask) {
-          const int t = r0 + rl;
-          const bool ok = rl < nv && kcol <= t && t < my_kend;
-          if (!ok) p = 0.f;
+      for (int e4 = 0; e4 < 4; ++e4) {
+        // accumulator values 4*e4 .. 4*e4+3 are four consecutive query rows
+        const int rl0 = 32 * mq + 8 * e4 + 4 * hh;
+        const f32x4 ls = *reinterpret_cast<const f32x4*>(lseS + rl0);
+        const f32x4 dl = *reinterpret_cast<const f32x4*>(dltS + rl0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int e = 4 * e4 + j;
+          float p = __builtin_amdgcn_exp2f(fmaf(S[e], sc, -ls[j]));
+          if (need_mask) {
+            const int t = r0 + rl0 + j;
+            const bool ok = rl0 + j < nv && kcol <= t && t < my_kend;
+            if (!ok) p = 0.f;
+          }
+          S[e] = p;
+          dP[e] = p * (dP[e] - dl[j]);
         }
-        S[e] = p;
-        dS[e] = p * (dP[e] - dltS[rl]);
       }
       const bf16x8 Pb0 = pack8(S, 0), Pb1 = pack8(S, 1);
-      const bf16x8 dSb0 = pack8(dS, 0), dSb1 = pack8(dS, 1);
+      const bf16x8 dSb0 = pack8(dP, 0), dSb1 = pack8(dP, 1);
 #pragma unroll
       for (int dmb = 0; dmb < 4; ++dmb) {
-        const bf16x8 dot0 = lds_read_col8(dOs, 32 * mq, 32 * dmb);
-        const bf16x8 dot1 = lds_read_col8(dOs, 32 * mq + 16, 32 * dmb);
+        const bf16x8 dot0 = lds_read_col8<kPitchBoth>(dOs, 32 * mq, 32 * dmb);
+        const bf16x8 dot1 = lds_read_col8<kPitchBoth>(dOs, 32 * mq + 16, 32 * dmb);
         dV[dmb] = mfma32(dot0, Pb0, dV[dmb]);
         dV[dmb] = mfma32(dot1, Pb1, dV[dmb]);
-        const bf16x8 qt0 = lds_read_col8(Qs, 32 * mq, 32 * dmb);
-        const bf16x8 qt1 = lds_read_col8(Qs, 32 * mq + 16, 32 * dmb);
+      }
+#pragma unroll
+      for (int dmb = 0; dmb < 4; ++dmb) {
+        const bf16x8 qt0 = lds_read_col8<kPitchBoth>(Qs, 32 * mq, 32 * dmb);
+        const bf16x8 qt1 = lds_read_col8<kPitchBoth>(Qs, 32 * mq + 16, 32 * dmb);
         dK[dmb] = mfma32(qt0, dSb0, dK[dmb]);
         dK[dmb] = mfma32(qt1, dSb1, dK[dmb]);
       }
@@ -357,14 +328,14 @@ int launch_bwd_bf16(const LaunchArgs& a) {
     { int ls = launch_status(__func__); if (ls != DTA_OK) return ls; }
   }
   if (a.stages & DTA_BWD_DQ) {
-    dq_bf16_kernel<<<(unsigned)qblocks, 256, 0, st>>>(
+    dq_bf16_kernel<<<(unsigned)qblocks, kDqThreads, 0, st>>>(
         a.sched->d_q_tiles, a.sched->d_segs, a.d_kend, (const uint16_t*)a.q, (const uint16_t*)a.k,
         (const uint16_t*)a.v, (const uint16_t*)a.d_o, a.lse_in, a.delta, (uint16_t*)a.dq,
         a.p.n_q_heads, a.p.n_kv_heads, a.tc.hb, a.tc.hblocks, a.p.softmax_scale);
     { int ls = launch_status(__func__); if (ls != DTA_OK) return ls; }
   }
   if (a.stages & DTA_BWD_DKDV) {
-    dkdv_bf16_kernel<<<(unsigned)kblocks, 256, 0, st>>>(
+    dkdv_bf16_kernel<<<(unsigned)kblocks, kKvThreads, 0, st>>>(
         a.sched->d_kv_tiles, a.d_kend, (const uint16_t*)a.q, (const uint16_t*)a.k,
         (const uint16_t*)a.v, (const uint16_t*)a.d_o, a.lse_in, a.delta, (uint16_t*)a.dk,
         (uint16_t*)a.dv, a.p.n_q_heads, a.p.n_kv_heads, a.p.softmax_scale);

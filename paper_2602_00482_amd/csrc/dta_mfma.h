@@ -16,10 +16,14 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
-// LDS tiles hold 128 bf16 per row plus 8 of padding: the 272-byte row pitch
-// keeps 16-byte row reads by 32 consecutive rows off the same banks.
+// LDS tiles hold 128 bf16 per row plus padding chosen for how the tile is read
+// (64 banks of 4 bytes).  16-byte row reads are served 16 lanes (rows) at a
+// time and need a row pitch of 4*odd banks; the transposing 8-byte reads are
+// served per 16-lane group (4 rows x 32 bytes) and need >= 8 banks between rows.
 constexpr int kHeadDim = 128;
-constexpr int kPitch = kHeadDim + 8;
+constexpr int kPitchRow = kHeadDim + 8;    // 68 banks  = 4 mod 64: row reads only
+constexpr int kPitchCol = kHeadDim + 32;   // 80 banks  = 16 mod 64: column (transposing) reads only
+constexpr int kPitchBoth = kHeadDim + 24;  // 76 banks  = 12 mod 64: both kinds of read
 
 // D(32x32) += A(32x16) * B(16x32), bf16 inputs, fp32 accumulate.
 // Lane l = (c = l % 32, hh = l / 32):
@@ -48,14 +52,15 @@ __device__ __forceinline__ s16x4 lds_read_tr4(const uint16_t* p) {
 // col0 + c of a row-major LDS tile.  This row order is exactly the order in
 // which a 32x32 accumulator block hands its 8 values v = 8s..8s+7 to the next
 // product when reused as the other operand (r0 = 16*s inside the block).
+template <int PITCH>
 __device__ __forceinline__ bf16x8 lds_read_col8(const uint16_t* tile, int r0, int col0) {
   const int l = threadIdx.x & 63;
   const int i = l & 15, g16 = l >> 4;
   const int hh = g16 >> 1;
   const int col = col0 + 16 * (g16 & 1) + 4 * (i & 3);
   const int row = r0 + 4 * hh + (i >> 2);
-  s16x4 lo = lds_read_tr4(tile + row * kPitch + col);
-  s16x4 hi = lds_read_tr4(tile + (row + 8) * kPitch + col);
+  s16x4 lo = lds_read_tr4(tile + row * PITCH + col);
+  s16x4 hi = lds_read_tr4(tile + (row + 8) * PITCH + col);
   union {
     struct { s16x4 a, b; } s;
     bf16x8 v;
@@ -73,16 +78,18 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& x, int s) {
 }
 
 // 64 rows x 128 bf16 from global (row pitch `stride` elements) into registers,
-// 16 bytes per thread per pass, 256 threads; rows >= nvalid come back as zeros.
+// 16 bytes per thread per pass, NT threads; rows >= nvalid come back as zeros.
+template <int NT>
 struct TileRegs {
-  uint4 r[4];
+  uint4 r[1024 / NT];
 };
 
-__device__ __forceinline__ void tile_load(TileRegs& t, const uint16_t* base, size_t stride,
+template <int NT>
+__device__ __forceinline__ void tile_load(TileRegs<NT>& t, const uint16_t* base, size_t stride,
                                           int nvalid) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int id = threadIdx.x + 256 * i;
+  for (int i = 0; i < 1024 / NT; ++i) {
+    const int id = threadIdx.x + NT * i;
     const int row = id >> 4, col = id & 15;
     if (row < nvalid)
       t.r[i] = *reinterpret_cast<const uint4*>(base + (size_t)row * stride + col * 8);
@@ -91,12 +98,13 @@ __device__ __forceinline__ void tile_load(TileRegs& t, const uint16_t* base, siz
   }
 }
 
-__device__ __forceinline__ void tile_store(const TileRegs& t, uint16_t* lds) {
+template <int PITCH, int NT>
+__device__ __forceinline__ void tile_store(const TileRegs<NT>& t, uint16_t* lds) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int id = threadIdx.x + 256 * i;
+  for (int i = 0; i < 1024 / NT; ++i) {
+    const int id = threadIdx.x + NT * i;
     const int row = id >> 4, col = id & 15;
-    *reinterpret_cast<uint4*>(lds + row * kPitch + col * 8) = t.r[i];
+    *reinterpret_cast<uint4*>(lds + row * PITCH + col * 8) = t.r[i];
   }
 }
 

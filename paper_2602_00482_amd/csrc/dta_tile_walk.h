@@ -1,0 +1,38 @@
+// Device-side walk over the key intervals of one query tile, shared by the
+// forward and dQ kernels.
+#pragma once
+
+#include "dta_internal.h"
+
+namespace dta {
+
+constexpr int kKeyChunk = 64;  // keys per streamed LDS tile
+
+// Yields the key intervals of a query tile in 64-key chunks: the pieces of the
+// tile's root path first (root to parent), the tile's own token range last.
+struct KeyChunks {
+  const KeySeg* segs;
+  int si, seg_end, t0, t1;
+  int cur, end, full;
+  __device__ __forceinline__ void load_seg() {
+    if (si < seg_end) {
+      cur = segs[si].start; end = segs[si].end; full = segs[si].full;
+    } else {
+      cur = t0; end = t1; full = 0;
+    }
+  }
+  __device__ __forceinline__ void init(const KeySeg* s, const QTile& t) {
+    segs = s; si = t.seg_begin; seg_end = t.seg_end; t0 = t.t0; t1 = t.t1;
+    load_seg();
+  }
+  // c0 = first key, n = keys in the chunk (<= 64), is_full = no mask needed
+  __device__ __forceinline__ bool next(int& c0, int& n, int& is_full) {
+    if (si > seg_end) return false;
+    c0 = cur; n = min(kKeyChunk, end - cur); is_full = full;
+    cur += kKeyChunk;
+    if (cur >= end) { ++si; if (si <= seg_end) load_seg(); }
+    return true;
+  }
+};
+
+}  // namespace dta

@@ -254,11 +254,11 @@ int choose_tiles(const dta_attn_params_t* p, TileChoice* out) {
     out->hb = 1;
     out->hblocks = G;
   } else {
-    // four waves per block: hb q heads of the group x (4/hb) 64-row query blocks
-    int hb = (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
+    // eight waves per block: hb q heads of the group x (8/hb) 32-row query blocks
+    int hb = (G % 8 == 0) ? 8 : (G % 4 == 0) ? 4 : (G % 2 == 0) ? 2 : 1;
     out->hb = hb;
     out->hblocks = G / hb;
-    out->bm = 64 * (4 / hb);
+    out->bm = 32 * (8 / hb);
     out->bn = 128;
   }
   return DTA_OK;
