@@ -64,9 +64,9 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
     const uint16_t* __restrict__ d_o, const float* __restrict__ lse,
     const float* __restrict__ delta, uint16_t* __restrict__ dq, int Hq, int Hkv, int HB,
     int hblocks, float scale) {
-  __shared__ __attribute__((aligned(16))) uint16_t Ks[kKeyChunk * kPitchBoth];
-  __shared__ __attribute__((aligned(16))) uint16_t Vs[kKeyChunk * kPitchRow];
-  __shared__ int32_t kendS[kKeyChunk];
+  __shared__ __attribute__((aligned(1024))) uint16_t Ks[2][kTileElems];
+  __shared__ __attribute__((aligned(1024))) uint16_t Vs[2][kTileElems];
+  __shared__ __attribute__((aligned(16))) int32_t kendS[2][kKeyChunk];
 
   const int inner = blockIdx.x % (Hkv * hblocks);
   const QTile tile = tiles[blockIdx.x / (Hkv * hblocks)];
@@ -102,28 +102,35 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
   const uint16_t* kbase = k + (size_t)g * kHeadDim;
   const uint16_t* vbase = v + (size_t)g * kHeadDim;
 
+  // chunk i lives in buffer i & 1 and is copied global -> LDS one iteration ahead
   KeyChunks it;
   it.init(segs, tile);
   int c0, n, full;
   bool have = it.next(c0, n, full);
-  TileRegs<kDqThreads> kreg, vreg;
-  tile_load(kreg, kbase + (size_t)c0 * kv_stride, kv_stride, n);
-  tile_load(vreg, vbase + (size_t)c0 * kv_stride, kv_stride, n);
+  auto issue = [&](int b) {
+    if (!full || n < kKeyChunk) {   // rare: a chunk that needs the visibility mask
+      if (threadIdx.x < kKeyChunk) {   // kendS is indexed by matrix position
+        const int row = row_of_pos(threadIdx.x);
+        kendS[b][threadIdx.x] = row >= n ? 0 : (full ? 0x7fffffff : kend[c0 + row]);
+      }
+    }
+    tile_async_load<kDqThreads>(Ks[b], kbase + (size_t)c0 * kv_stride, kv_stride, n);
+    tile_async_load<kDqThreads>(Vs[b], vbase + (size_t)c0 * kv_stride, kv_stride, n);
+  };
+  issue(0);
+  int buf = 0;
+  const int rlo = row_lane_off(), clo = col_lane_off();
 
   while (have) {
-    __syncthreads();
-    tile_store<kPitchBoth>(kreg, Ks);
-    tile_store<kPitchRow>(vreg, Vs);
-    if (!full && threadIdx.x < kKeyChunk)
-      kendS[threadIdx.x] = (int)threadIdx.x < n ? kend[c0 + threadIdx.x] : 0;
-    __syncthreads();
-    const int cc0 = c0, cn = n, cfull = full;
+    async_wait_all();
+    __syncthreads();   // chunk `buf` has landed; everyone is done with the other buffer
+    const int cc0 = c0;
+    const bool need_mask = !full || n < kKeyChunk;
     have = it.next(c0, n, full);
-    if (have) {
-      tile_load(kreg, kbase + (size_t)c0 * kv_stride, kv_stride, n);
-      tile_load(vreg, vbase + (size_t)c0 * kv_stride, kv_stride, n);
-    }
-    const bool need_mask = !cfull || cn < kKeyChunk;
+    if (have) issue(buf ^ 1);
+    const uint16_t* Kt = Ks[buf] + rlo;
+    const uint16_t* Vt = Vs[buf] + rlo;
+    const uint16_t* Kc = Ks[buf] + clo;
 
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb) {
@@ -132,32 +139,40 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
       for (int e = 0; e < 16; ++e) { S[e] = 0.f; dP[e] = 0.f; }
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 ka = lds_read_row8(Ks + (32 * mb + c) * kPitchBoth + 16 * ks + 8 * hh);
-        const bf16x8 va = lds_read_row8(Vs + (32 * mb + c) * kPitchRow + 16 * ks + 8 * hh);
+        const bf16x8 ka = tile_row8(Kt, mb, ks);
+        const bf16x8 va = tile_row8(Vt, mb, ks);
         S = mfma32(ka, Qr[ks], S);
         dP = mfma32(va, dOr[ks], dP);
       }
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        float p = __builtin_amdgcn_exp2f(fmaf(S[e], sc, -lse2));
+      for (int e4 = 0; e4 < 4; ++e4) {
+        int kev[4] = {0, 0, 0, 0};
         if (need_mask) {
-          const int kvl = 32 * mb + 8 * (e / 4) + 4 * hh + (e % 4);
-          const int ke = cfull ? 0x7fffffff : kendS[kvl];
-          const bool ok = kvl < cn && (cfull || cc0 + kvl <= qrow) && qrow < ke;
-          if (!ok) p = 0.f;
+          const int4 ke = *reinterpret_cast<const int4*>(&kendS[buf][32 * mb + 8 * e4 + 4 * hh]);
+          kev[0] = ke.x; kev[1] = ke.y; kev[2] = ke.z; kev[3] = ke.w;
         }
-        S[e] = p * (dP[e] - dlt);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int e = 4 * e4 + j;
+          float p = __builtin_amdgcn_exp2f(fmaf(S[e], sc, -lse2));
+          if (need_mask) {
+            const bool ok = (cc0 + row_of_acc(mb, e, hh) <= qrow) & (qrow < kev[j]);
+            p = ok ? p : 0.f;
+          }
+          S[e] = p * (dP[e] - dlt);
+        }
       }
       const bf16x8 dSb0 = pack8(S, 0), dSb1 = pack8(S, 1);
       // dQ^T += K^T dS^T over this 32-key half
 #pragma unroll
       for (int dmb = 0; dmb < 4; ++dmb) {
-        const bf16x8 kt0 = lds_read_col8<kPitchBoth>(Ks, 32 * mb, 32 * dmb);
-        const bf16x8 kt1 = lds_read_col8<kPitchBoth>(Ks, 32 * mb + 16, 32 * dmb);
+        const bf16x8 kt0 = tile_col8(Kc, 32 * mb, 32 * dmb);
+        const bf16x8 kt1 = tile_col8(Kc, 32 * mb + 16, 32 * dmb);
         dQ[dmb] = mfma32(kt0, dSb0, dQ[dmb]);
         dQ[dmb] = mfma32(kt1, dSb1, dQ[dmb]);
       }
     }
+    buf ^= 1;
   }
 
   const int token = row_base + c;
@@ -186,10 +201,10 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
     const uint16_t* __restrict__ v, const uint16_t* __restrict__ d_o,
     const float* __restrict__ lse, const float* __restrict__ delta, uint16_t* __restrict__ dk,
     uint16_t* __restrict__ dv, int Hq, int Hkv, float scale) {
-  __shared__ __attribute__((aligned(16))) uint16_t Qs[kBQ * kPitchBoth];
-  __shared__ __attribute__((aligned(16))) uint16_t dOs[kBQ * kPitchBoth];
-  __shared__ __attribute__((aligned(16))) float lseS[kBQ];
-  __shared__ __attribute__((aligned(16))) float dltS[kBQ];
+  __shared__ __attribute__((aligned(1024))) uint16_t Qs[2][kTileElems];
+  __shared__ __attribute__((aligned(1024))) uint16_t dOs[2][kTileElems];
+  __shared__ __attribute__((aligned(16))) float lseS[2][kBQ];
+  __shared__ __attribute__((aligned(16))) float dltS[2][kBQ];
 
   const KvTile tile = tiles[blockIdx.x / Hkv];
   const int g = blockIdx.x % Hkv;
@@ -219,31 +234,41 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
     for (int e = 0; e < 16; ++e) { dK[a][e] = 0.f; dV[a][e] = 0.f; }
 
   const size_t q_stride = (size_t)Hq * kHeadDim;
-  // flat iteration over (head of the group, 64-row query chunk)
+  // flat iteration over (head of the group, 64-row query chunk); chunk `it` lives
+  // in buffer it & 1 and is copied global -> LDS one iteration ahead of its use
   const int n_chunks = (tile.q_end - tile.k0 + kBQ - 1) / kBQ;
   const int total = n_chunks * G;
-
-  for (int it = 0; it < total; ++it) {
+  float lse_r = 0.f, dlt_r = 0.f;   // travel through registers, stored a step later
+  auto issue = [&](int it, int b) {
     const int hsub = it / n_chunks, ch = it - hsub * n_chunks;
     const int h = g * G + hsub;
     const int r0 = tile.k0 + ch * kBQ;
     const int nv = min(kBQ, tile.q_end - r0);
-    {
-      TileRegs<kKvThreads> qreg, doreg;
-      tile_load(qreg, q + (size_t)r0 * q_stride + (size_t)h * kHeadDim, q_stride, nv);
-      tile_load(doreg, d_o + (size_t)r0 * q_stride + (size_t)h * kHeadDim, q_stride, nv);
-      float lse_r = 0.f, dlt_r = 0.f;
-      if (threadIdx.x < kBQ && (int)threadIdx.x < nv) {
-        lse_r = lse[(size_t)(r0 + threadIdx.x) * Hq + h] * kLog2e;
-        dlt_r = delta[(size_t)(r0 + threadIdx.x) * Hq + h];
-      }
-      __syncthreads();   // every wave is done reading the previous chunk
-      tile_store<kPitchBoth>(qreg, Qs);
-      tile_store<kPitchBoth>(doreg, dOs);
-      if (threadIdx.x < kBQ) { lseS[threadIdx.x] = lse_r; dltS[threadIdx.x] = dlt_r; }
-      __syncthreads();
+    if (threadIdx.x < kBQ) {   // lseS / dltS are indexed by matrix position
+      const size_t idx = (size_t)min(r0 + row_of_pos(threadIdx.x), tile.q_end - 1) * Hq + h;
+      lse_r = lse[idx] * kLog2e;
+      dlt_r = delta[idx];
     }
+    tile_async_load<kKvThreads>(Qs[b], q + (size_t)r0 * q_stride + (size_t)h * kHeadDim, q_stride, nv);
+    tile_async_load<kKvThreads>(dOs[b], d_o + (size_t)r0 * q_stride + (size_t)h * kHeadDim, q_stride, nv);
+  };
+  if (total > 0) issue(0, 0);
+  int buf = 0;
+  const int rlo = row_lane_off(), clo = col_lane_off();
+
+  for (int it = 0; it < total; ++it) {
+    async_wait_all();
+    if (threadIdx.x < kBQ) { lseS[buf][threadIdx.x] = lse_r; dltS[buf][threadIdx.x] = dlt_r; }
+    __syncthreads();   // chunk `buf` has landed; everyone is done with the other buffer
+    if (it + 1 < total) issue(it + 1, buf ^ 1);
+    const int ch = it % n_chunks;
+    const int r0 = tile.k0 + ch * kBQ;
+    const int nv = min(kBQ, tile.q_end - r0);
     const bool need_mask = !(r0 >= tile.k1 && r0 + kBQ <= tile.q_full_end);
+    const uint16_t* Qt = Qs[buf] + rlo;
+    const uint16_t* dOt = dOs[buf] + rlo;
+    const uint16_t* Qc = Qs[buf] + clo;
+    const uint16_t* dOc = dOs[buf] + clo;
 
 #pragma unroll
     for (int mq = 0; mq < 2; ++mq) {
@@ -252,25 +277,26 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
       for (int e = 0; e < 16; ++e) { S[e] = 0.f; dP[e] = 0.f; }
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 qa = lds_read_row8(Qs + (32 * mq + c) * kPitchBoth + 16 * ks + 8 * hh);
-        const bf16x8 da = lds_read_row8(dOs + (32 * mq + c) * kPitchBoth + 16 * ks + 8 * hh);
+        const bf16x8 qa = tile_row8(Qt, mq, ks);
+        const bf16x8 da = tile_row8(dOt, mq, ks);
         S = mfma32(qa, Kr[ks], S);
         dP = mfma32(da, Vr[ks], dP);
       }
 #pragma unroll
       for (int e4 = 0; e4 < 4; ++e4) {
-        // accumulator values 4*e4 .. 4*e4+3 are four consecutive query rows
+        // accumulator values 4*e4 .. 4*e4+3 are four consecutive matrix positions
         const int rl0 = 32 * mq + 8 * e4 + 4 * hh;
-        const f32x4 ls = *reinterpret_cast<const f32x4*>(lseS + rl0);
-        const f32x4 dl = *reinterpret_cast<const f32x4*>(dltS + rl0);
+        const f32x4 ls = *reinterpret_cast<const f32x4*>(&lseS[buf][rl0]);
+        const f32x4 dl = *reinterpret_cast<const f32x4*>(&dltS[buf][rl0]);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const int e = 4 * e4 + j;
           float p = __builtin_amdgcn_exp2f(fmaf(S[e], sc, -ls[j]));
           if (need_mask) {
-            const int t = r0 + rl0 + j;
-            const bool ok = rl0 + j < nv && kcol <= t && t < my_kend;
-            if (!ok) p = 0.f;
+            const int rl = row_of_acc(mq, e, hh);
+            const int t = r0 + rl;
+            const bool ok = (rl < nv) & (kcol <= t) & (t < my_kend);
+            p = ok ? p : 0.f;
           }
           S[e] = p;
           dP[e] = p * (dP[e] - dl[j]);
@@ -280,19 +306,20 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
       const bf16x8 dSb0 = pack8(dP, 0), dSb1 = pack8(dP, 1);
 #pragma unroll
       for (int dmb = 0; dmb < 4; ++dmb) {
-        const bf16x8 dot0 = lds_read_col8<kPitchBoth>(dOs, 32 * mq, 32 * dmb);
-        const bf16x8 dot1 = lds_read_col8<kPitchBoth>(dOs, 32 * mq + 16, 32 * dmb);
+        const bf16x8 dot0 = tile_col8(dOc, 32 * mq, 32 * dmb);
+        const bf16x8 dot1 = tile_col8(dOc, 32 * mq + 16, 32 * dmb);
         dV[dmb] = mfma32(dot0, Pb0, dV[dmb]);
         dV[dmb] = mfma32(dot1, Pb1, dV[dmb]);
       }
 #pragma unroll
       for (int dmb = 0; dmb < 4; ++dmb) {
-        const bf16x8 qt0 = lds_read_col8<kPitchBoth>(Qs, 32 * mq, 32 * dmb);
-        const bf16x8 qt1 = lds_read_col8<kPitchBoth>(Qs, 32 * mq + 16, 32 * dmb);
+        const bf16x8 qt0 = tile_col8(Qc, 32 * mq, 32 * dmb);
+        const bf16x8 qt1 = tile_col8(Qc, 32 * mq + 16, 32 * dmb);
         dK[dmb] = mfma32(qt0, dSb0, dK[dmb]);
         dK[dmb] = mfma32(qt1, dSb1, dK[dmb]);
       }
     }
+    buf ^= 1;
   }
 
   if (kcol < tile.k1) {

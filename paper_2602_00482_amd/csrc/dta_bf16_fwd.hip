@@ -29,9 +29,9 @@ __global__ __launch_bounds__(kThreads) void fwd_bf16_kernel(
     const int32_t* __restrict__ kend, const uint16_t* __restrict__ q,
     const uint16_t* __restrict__ k, const uint16_t* __restrict__ v, uint16_t* __restrict__ o,
     float* __restrict__ lse, int Hq, int Hkv, int HB, int hblocks, float scale) {
-  __shared__ __attribute__((aligned(16))) uint16_t Ks[kKeyChunk * kPitchRow];
-  __shared__ __attribute__((aligned(16))) uint16_t Vs[kKeyChunk * kPitchCol];
-  __shared__ int32_t kendS[kKeyChunk];
+  __shared__ __attribute__((aligned(1024))) uint16_t Ks[2][kTileElems];
+  __shared__ __attribute__((aligned(1024))) uint16_t Vs[2][kTileElems];
+  __shared__ __attribute__((aligned(16))) int32_t kendS[2][kKeyChunk];
 
   const int inner = blockIdx.x % (Hkv * hblocks);
   const QTile tile = tiles[blockIdx.x / (Hkv * hblocks)];
@@ -70,27 +70,35 @@ __global__ __launch_bounds__(kThreads) void fwd_bf16_kernel(
   const uint16_t* kbase = k + (size_t)g * kHeadDim;
   const uint16_t* vbase = v + (size_t)g * kHeadDim;
 
+  // Chunk i lives in buffer i & 1 and is copied global -> LDS one iteration ahead
+  // of its use, so one barrier per chunk is enough.
   KeyChunks it;
   it.init(segs, tile);
   int c0, n, full;
   bool have = it.next(c0, n, full);
-  TileRegs<kThreads> kreg, vreg;
-  tile_load(kreg, kbase + (size_t)c0 * kv_stride, kv_stride, n);
-  tile_load(vreg, vbase + (size_t)c0 * kv_stride, kv_stride, n);
+  auto issue = [&](int b) {
+    if (!full || n < kKeyChunk) {   // rare: a chunk that needs the visibility mask
+      if (threadIdx.x < kKeyChunk) {   // kendS is indexed by matrix position
+        const int row = row_of_pos(threadIdx.x);
+        kendS[b][threadIdx.x] = row >= n ? 0 : (full ? 0x7fffffff : kend[c0 + row]);
+      }
+    }
+    tile_async_load<kThreads>(Ks[b], kbase + (size_t)c0 * kv_stride, kv_stride, n);
+    tile_async_load<kThreads>(Vs[b], vbase + (size_t)c0 * kv_stride, kv_stride, n);
+  };
+  issue(0);
+  int buf = 0;
+  const int rlo = row_lane_off(), clo = col_lane_off();
 
   while (have) {
-    __syncthreads();
-    tile_store<kPitchRow>(kreg, Ks);
-    tile_store<kPitchCol>(vreg, Vs);
-    if (!full && threadIdx.x < kKeyChunk)
-      kendS[threadIdx.x] = (int)threadIdx.x < n ? kend[c0 + threadIdx.x] : 0;
-    __syncthreads();
-    const int cc0 = c0, cn = n, cfull = full;
+    async_wait_all();
+    __syncthreads();   // chunk `buf` has landed; everyone is done with the other buffer
+    const int cc0 = c0;
+    const bool need_mask = !full || n < kKeyChunk;
     have = it.next(c0, n, full);
-    if (have) {
-      tile_load(kreg, kbase + (size_t)c0 * kv_stride, kv_stride, n);
-      tile_load(vreg, vbase + (size_t)c0 * kv_stride, kv_stride, n);
-    }
+    if (have) issue(buf ^ 1);
+    const uint16_t* Kt = Ks[buf] + rlo;
+    const uint16_t* Vt = Vs[buf] + clo;
 
     // ---- S^T = K Q^T : 64 keys x 32 queries
     f32x16 S[2];
@@ -100,22 +108,28 @@ __global__ __launch_bounds__(kThreads) void fwd_bf16_kernel(
       for (int e = 0; e < 16; ++e) S[a][e] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-      const bf16x8 a0 = lds_read_row8(Ks + c * kPitchRow + 16 * ks + 8 * hh);
-      const bf16x8 a1 = lds_read_row8(Ks + (32 + c) * kPitchRow + 16 * ks + 8 * hh);
+      const bf16x8 a0 = tile_row8(Kt, 0, ks);
+      const bf16x8 a1 = tile_row8(Kt, 1, ks);
       S[0] = mfma32(a0, Qr[ks], S[0]);
       S[1] = mfma32(a1, Qr[ks], S[1]);
     }
 
-    // ---- mask
-    if (!cfull || cn < kKeyChunk) {
+    // ---- mask: key kv is visible to row t iff kv <= t < kend[kv]; kendS holds
+    // 0 for padding keys and INT_MAX for keys every row of the tile sees (those
+    // lie before the tile, so the causal test is true for them anyway)
+    if (need_mask) {
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int kvl = 32 * mb + 8 * (e / 4) + 4 * hh + (e % 4);
-          const int ke = cfull ? 0x7fffffff : kendS[kvl];
-          const bool ok = kvl < cn && (cfull || cc0 + kvl <= qrow) && qrow < ke;
-          if (!ok) S[mb][e] = -INFINITY;
+        for (int e4 = 0; e4 < 4; ++e4) {
+          const int kvl0 = 32 * mb + 8 * e4 + 4 * hh;
+          const int4 ke = *reinterpret_cast<const int4*>(&kendS[buf][kvl0]);
+          const int kev[4] = {ke.x, ke.y, ke.z, ke.w};
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const bool ok = (cc0 + row_of_acc(mb, 4 * e4 + j, hh) <= qrow) & (qrow < kev[j]);
+            S[mb][4 * e4 + j] = ok ? S[mb][4 * e4 + j] : -INFINITY;
+          }
         }
     }
 
@@ -158,10 +172,11 @@ __global__ __launch_bounds__(kThreads) void fwd_bf16_kernel(
     for (int kk = 0; kk < 4; ++kk) {
 #pragma unroll
       for (int dmb = 0; dmb < 4; ++dmb) {
-        const bf16x8 va = lds_read_col8<kPitchCol>(Vs, 16 * kk, 32 * dmb);
+        const bf16x8 va = tile_col8(Vt, 16 * kk, 32 * dmb);
         O[dmb] = mfma32(va, Pb[kk], O[dmb]);
       }
     }
+    buf ^= 1;
   }
 
   // ---- normalise and store

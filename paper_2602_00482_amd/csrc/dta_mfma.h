@@ -108,4 +108,84 @@ __device__ __forceinline__ void tile_store(const TileRegs<NT>& t, uint16_t* lds)
   }
 }
 
+
+// ---- tiles filled by direct global-to-LDS loads -------------------------------
+// A wave's 16-byte direct loads land in 1 KB of consecutive LDS = 4 rows of 128
+// bf16, so padding is only possible between such 4-row groups.  Bank conflicts
+// are avoided by choosing WHICH tile row each matrix position uses: the matrix
+// products only need keys (or query rows) to sit at consistent positions, not in
+// order.  Position x (0..63) of a product uses tile row
+//     row_of_pos(x) = 4 * sigma(x & 15) + (x >> 4),  sigma(y) = 2 * (y & 7) + (y >> 3),
+// and group g starts at g * 1040 bytes.  Then the 16 lanes of one pass of a
+// 16-byte row read touch 16 different groups (16 different 16-byte bank offsets),
+// the 4 rows of one pass of a transposing read sit 32 bytes of bank offset apart,
+// and every read address is a per-lane base plus a compile-time constant.
+constexpr int kGroupPitch = 4 * kHeadDim + 8;     // elements between 4-row groups (1040 bytes)
+constexpr int kTileElems = 16 * kGroupPitch;      // one 64 x 128 tile
+
+__device__ __forceinline__ int sigma16(int y) { return ((y & 7) << 1) | (y >> 3); }
+__device__ __forceinline__ int row_of_pos(int x) { return 4 * sigma16(x & 15) + (x >> 4); }
+// For lane half hh, accumulator value e (0..15) of 32-position block mb holds
+// position 32*mb + 8*(e/4) + 4*hh + e%4, i.e. tile row
+__device__ __forceinline__ int row_of_acc(int mb, int e, int hh) {
+  return 32 * hh + 8 * (e & 3) + 4 * ((e >> 2) & 1) + (e >> 3) + 2 * mb;
+}
+
+// Starts the copy of rows [0, 64) x 128 bf16 (global row pitch `stride` elements)
+// into `tile`; rows >= nvalid re-read row nvalid-1 (finite data the mask hides).
+// Completion: async_wait_all() by every thread, then a block barrier.
+template <int NT>
+__device__ __forceinline__ void tile_async_load(uint16_t* tile, const uint16_t* base, size_t stride,
+                                                int nvalid) {
+  constexpr int NW = NT / 64;
+  const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
+#pragma unroll
+  for (int p = 0; p < 16 / NW; ++p) {
+    const int grp = w + NW * p;
+    const int row = 4 * grp + (l >> 4);
+    const uint16_t* g = base + (size_t)min(row, nvalid - 1) * stride + (l & 15) * 8;
+    // Written as inline assembly on purpose: for the builtin form the compiler
+    // drains every outstanding load before the next LDS read, which would undo
+    // the prefetch.  LDS destination = M0 + 16 * lane.
+    const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(
+        (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(tile + grp * kGroupPitch));
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(g), "s"(lds_addr)
+                 : "memory");
+  }
+}
+
+__device__ __forceinline__ void async_wait_all() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// Per-lane element offsets into a tile; add compile-time constants per read.
+// Row operand (lane = position c of a 32-block, half hh): 8 elements at
+//   tile + row_lane_off() + 256 * mb + 16 * ks          (block mb, k-step ks)
+__device__ __forceinline__ int row_lane_off() {
+  const int l = threadIdx.x & 63, c = l & 31, hh = l >> 5;
+  return sigma16(c & 15) * kGroupPitch + (c >> 4) * kHeadDim + hh * 8;
+}
+// Column operand (contraction over positions r0 .. r0+15, r0 a multiple of 16,
+// columns col0 .. col0+31): same value order as lds_read_col8, at
+//   tile + col_lane_off() + 128 * (r0 / 16) + col0   and   + kGroupPitch for the upper 8
+__device__ __forceinline__ int col_lane_off() {
+  const int l = threadIdx.x & 63, i = l & 15, g16 = l >> 4, hh = g16 >> 1;
+  return sigma16(4 * hh + (i >> 2)) * kGroupPitch + 16 * (g16 & 1) + 4 * (i & 3);
+}
+__device__ __forceinline__ bf16x8 tile_row8(const uint16_t* lane_ptr, int mb, int ks) {
+  return *reinterpret_cast<const bf16x8*>(lane_ptr + 256 * mb + 16 * ks);
+}
+__device__ __forceinline__ bf16x8 tile_col8(const uint16_t* lane_ptr, int r0, int col0) {
+  const uint16_t* p = lane_ptr + kHeadDim * (r0 >> 4) + col0;
+  s16x4 lo = lds_read_tr4(p);
+  s16x4 hi = lds_read_tr4(p + kGroupPitch);
+  union {
+    struct { s16x4 a, b; } s;
+    bf16x8 v;
+  } u;
+  u.s.a = lo;
+  u.s.b = hi;
+  return u.v;
+}
+
 }  // namespace dta

@@ -25,6 +25,12 @@ struct KeyChunks {
     segs = s; si = t.seg_begin; seg_end = t.seg_end; t0 = t.t0; t1 = t.t1;
     load_seg();
   }
+  // number of chunks the walk will yield
+  __device__ __forceinline__ static int count(const KeySeg* s, const QTile& t) {
+    int nch = (t.t1 - t.t0 + kKeyChunk - 1) / kKeyChunk;
+    for (int i = t.seg_begin; i < t.seg_end; ++i) nch += (s[i].end - s[i].start + kKeyChunk - 1) / kKeyChunk;
+    return nch;
+  }
   // c0 = first key, n = keys in the chunk (<= 64), is_full = no mask needed
   __device__ __forceinline__ bool next(int& c0, int& n, int& is_full) {
     if (si > seg_end) return false;
