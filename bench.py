@@ -68,7 +68,10 @@ class Runner:
         self.dq = torch.empty_like(self.q)
         self.dk = torch.empty_like(self.k)
         self.dv = torch.empty_like(self.v)
-        self.ws = torch.empty(max(256, self.T * self.Hq * 4 + 256), dtype=torch.uint8, device="cuda")
+        tree = dta.tree_build(parent, seg)
+        self.ws = torch.empty(max(256, dta.workspace_bytes(tree, self.params, True)), dtype=torch.uint8,
+                              device="cuda")
+        tree.destroy()
 
     def step(self):
         dta = self.dta

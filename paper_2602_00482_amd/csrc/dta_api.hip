@@ -15,6 +15,22 @@ size_t delta_bytes(const dta_tree* tree, const dta_attn_params_t* p) {
   return round_up((size_t)tree->info.n_tokens * (size_t)p->n_q_heads * sizeof(float), 256);
 }
 
+// delta plus, in bf16 mode, the partial sums of split key tiles (building the
+// host schedule if this head configuration has not been seen yet)
+size_t bwd_workspace_bytes(dta_tree* tree, const dta::TileChoice& tc, const dta_attn_params_t* p) {
+  size_t bytes = delta_bytes(tree, p);
+  if (p->dtype == DTA_BF16) {
+    try {
+      std::lock_guard<std::mutex> lock(tree->mu);
+      bytes += dta::partial_bytes(
+          dta::get_schedule(tree, tc.bm, tc.bn, p->n_kv_heads, p->n_q_heads / p->n_kv_heads));
+    } catch (const std::bad_alloc&) {
+      return 0;
+    }
+  }
+  return bytes;
+}
+
 template <typename T>
 int upload(const std::vector<T>& host, T** dev) {
   if (*dev) {
@@ -41,7 +57,8 @@ int upload(const std::vector<T>& host, T** dev) {
 
 // Makes sure the schedule for (bm, bn) and kend[] are resident on the current
 // device.  Takes the tree lock; blocking on first use, a no-op afterwards.
-int ensure_device(dta_tree* tree, const dta::TileChoice& tc, dta::Schedule** out) {
+int ensure_device(dta_tree* tree, const dta::TileChoice& tc, const dta_attn_params_t* p,
+                  dta::Schedule** out) {
   std::lock_guard<std::mutex> lock(tree->mu);
   int dev = -1;
   if (hipGetDevice(&dev) != hipSuccess) {
@@ -51,7 +68,7 @@ int ensure_device(dta_tree* tree, const dta::TileChoice& tc, dta::Schedule** out
   }
   dta::Schedule* s;
   try {
-    s = &dta::get_schedule(tree, tc.bm, tc.bn);
+    s = &dta::get_schedule(tree, tc.bm, tc.bn, p->n_kv_heads, p->n_q_heads / p->n_kv_heads);
   } catch (const std::bad_alloc&) {
     return DTA_ERR_ALLOC;
   }
@@ -64,6 +81,8 @@ int ensure_device(dta_tree* tree, const dta::TileChoice& tc, dta::Schedule** out
     if ((st = upload(s->q_tiles, &s->d_q_tiles)) != DTA_OK) return st;
     if ((st = upload(s->segs, &s->d_segs)) != DTA_OK) return st;
     if ((st = upload(s->kv_tiles, &s->d_kv_tiles)) != DTA_OK) return st;
+    if ((st = upload(s->kv_items, &s->d_kv_items)) != DTA_OK) return st;
+    if ((st = upload(s->kv_reduce, &s->d_kv_reduce)) != DTA_OK) return st;
     s->device = dev;
   }
   *out = s;
@@ -97,14 +116,18 @@ void dta_tree_destroy(dta_tree_t* tree) {
     if (s.d_q_tiles) (void)hipFree(s.d_q_tiles);
     if (s.d_segs) (void)hipFree(s.d_segs);
     if (s.d_kv_tiles) (void)hipFree(s.d_kv_tiles);
+    if (s.d_kv_items) (void)hipFree(s.d_kv_items);
+    if (s.d_kv_reduce) (void)hipFree(s.d_kv_reduce);
   }
   delete tree;
 }
 
 size_t dta_tree_attn_workspace_bytes(const dta_tree_t* tree, const dta_attn_params_t* params,
                                      int is_bwd) {
-  if (!tree || dta::validate_params(params) != DTA_OK) return 0;
-  return is_bwd ? delta_bytes(tree, params) : 0;
+  dta::TileChoice tc;
+  if (!tree || dta::choose_tiles(params, &tc) != DTA_OK) return 0;
+  if (!is_bwd) return 0;
+  return bwd_workspace_bytes(const_cast<dta_tree*>(tree), tc, params);
 }
 
 int dta_tree_attn_prepare(dta_tree_t* tree, const dta_attn_params_t* params) {
@@ -113,7 +136,7 @@ int dta_tree_attn_prepare(dta_tree_t* tree, const dta_attn_params_t* params) {
   int st = dta::choose_tiles(params, &tc);
   if (st != DTA_OK) return st;
   dta::Schedule* s = nullptr;
-  return ensure_device(tree, tc, &s);
+  return ensure_device(tree, tc, params, &s);
 }
 
 int dta_tree_attn_fwd(dta_tree_t* tree, const dta_attn_params_t* params, const void* q,
@@ -129,7 +152,7 @@ int dta_tree_attn_fwd(dta_tree_t* tree, const dta_attn_params_t* params, const v
   if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse))
     return DTA_ERR_INVALID_ARG;
   dta::Schedule* s = nullptr;
-  if ((st = ensure_device(tree, tc, &s)) != DTA_OK) return st;
+  if ((st = ensure_device(tree, tc, params, &s)) != DTA_OK) return st;
   dta::LaunchArgs a{};
   a.tree = tree;
   a.sched = s;
@@ -160,10 +183,11 @@ int dta_tree_attn_bwd_stages(dta_tree_t* tree, const dta_attn_params_t* params, 
   if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse) ||
       misaligned(d_o) || misaligned(dq) || misaligned(dk) || misaligned(dv))
     return DTA_ERR_INVALID_ARG;
-  if (!workspace || workspace_bytes < delta_bytes(tree, params) || ((uintptr_t)workspace & 255u))
+  if (!workspace || workspace_bytes < bwd_workspace_bytes(tree, tc, params) ||
+      ((uintptr_t)workspace & 255u))
     return DTA_ERR_WORKSPACE;
   dta::Schedule* s = nullptr;
-  if ((st = ensure_device(tree, tc, &s)) != DTA_OK) return st;
+  if ((st = ensure_device(tree, tc, params, &s)) != DTA_OK) return st;
   dta::LaunchArgs a{};
   a.tree = tree;
   a.sched = s;
@@ -180,6 +204,7 @@ int dta_tree_attn_bwd_stages(dta_tree_t* tree, const dta_attn_params_t* params, 
   a.dk = dk;
   a.dv = dv;
   a.delta = (float*)workspace;
+  a.partial = (float*)((char*)workspace + delta_bytes(tree, params));
   a.stages = stage_mask;
   a.stream = hip_stream;
   return params->dtype == DTA_F32 ? dta::launch_bwd_f32(a) : dta::launch_bwd_bf16(a);

@@ -191,22 +191,23 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
 }
 
 constexpr int kKvThreads = 256;
+constexpr int kKvTile = 128;   // keys per dK/dV tile (32 per wave)
 
 // Key-stationary dK/dV: 4 waves, 32 key columns each, K and V rows in
 // registers.  Two blocks share a CU (everything fits in 256 registers), so one
 // block's global loads and barriers are covered by the other's matrix work.
 __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
-    const KvTile* __restrict__ tiles, const int32_t* __restrict__ kend,
+    const KvItem* __restrict__ items, const int32_t* __restrict__ kend,
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, const uint16_t* __restrict__ d_o,
     const float* __restrict__ lse, const float* __restrict__ delta, uint16_t* __restrict__ dk,
-    uint16_t* __restrict__ dv, int Hq, int Hkv, float scale) {
+    uint16_t* __restrict__ dv, float* __restrict__ partial, int Hq, int Hkv, float scale) {
   __shared__ __attribute__((aligned(1024))) uint16_t Qs[2][kTileElems];
   __shared__ __attribute__((aligned(1024))) uint16_t dOs[2][kTileElems];
   __shared__ __attribute__((aligned(16))) float lseS[2][kBQ];
   __shared__ __attribute__((aligned(16))) float dltS[2][kBQ];
 
-  const KvTile tile = tiles[blockIdx.x / Hkv];
+  const KvItem tile = items[blockIdx.x / Hkv];
   const int g = blockIdx.x % Hkv;
   const int G = Hq / Hkv;
   const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
@@ -236,8 +237,9 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
   const size_t q_stride = (size_t)Hq * kHeadDim;
   // flat iteration over (head of the group, 64-row query chunk); chunk `it` lives
   // in buffer it & 1 and is copied global -> LDS one iteration ahead of its use
+  // (this item covers iterations [it_begin, it_end) of the tile's walk)
   const int n_chunks = (tile.q_end - tile.k0 + kBQ - 1) / kBQ;
-  const int total = n_chunks * G;
+  const int total = tile.it_end;
   float lse_r = 0.f, dlt_r = 0.f;   // travel through registers, stored a step later
   auto issue = [&](int it, int b) {
     const int hsub = it / n_chunks, ch = it - hsub * n_chunks;
@@ -252,11 +254,11 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
     tile_async_load<kKvThreads>(Qs[b], q + (size_t)r0 * q_stride + (size_t)h * kHeadDim, q_stride, nv);
     tile_async_load<kKvThreads>(dOs[b], d_o + (size_t)r0 * q_stride + (size_t)h * kHeadDim, q_stride, nv);
   };
-  if (total > 0) issue(0, 0);
+  if (tile.it_begin < total) issue(tile.it_begin, 0);
   int buf = 0;
   const int rlo = row_lane_off(), clo = col_lane_off();
 
-  for (int it = 0; it < total; ++it) {
+  for (int it = tile.it_begin; it < total; ++it) {
     async_wait_all();
     if (threadIdx.x < kBQ) { lseS[buf][threadIdx.x] = lse_r; dltS[buf][threadIdx.x] = dlt_r; }
     __syncthreads();   // chunk `buf` has landed; everyone is done with the other buffer
@@ -322,7 +324,22 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
     buf ^= 1;
   }
 
-  if (kcol < tile.k1) {
+  if (tile.slot >= 0) {
+    // one of several items of this key tile: fp32 partial sums, [dK | dV] x 128 keys x 128
+    float* pk = partial + ((size_t)tile.slot * Hkv + g) * (2 * kKvTile * kHeadDim) +
+                (size_t)(32 * w + c) * kHeadDim + 4 * hh;
+    float* pv = pk + kKvTile * kHeadDim;
+#pragma unroll
+    for (int dmb = 0; dmb < 4; ++dmb)
+#pragma unroll
+      for (int v4 = 0; v4 < 4; ++v4) {
+        f32x4 rk, rv;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { rk[e] = dK[dmb][4 * v4 + e]; rv[e] = dV[dmb][4 * v4 + e]; }
+        *reinterpret_cast<f32x4*>(pk + 32 * dmb + 8 * v4) = rk;
+        *reinterpret_cast<f32x4*>(pv + 32 * dmb + 8 * v4) = rv;
+      }
+  } else if (kcol < tile.k1) {
     const size_t base = ((size_t)kcol * Hkv + g) * kHeadDim + 4 * hh;
 #pragma unroll
     for (int dmb = 0; dmb < 4; ++dmb)
@@ -340,6 +357,36 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
   }
 }
 
+// Adds the partial sums of a split key tile in slot order and writes dK/dV.
+__global__ __launch_bounds__(256) void dkdv_reduce_kernel(const KvReduce* __restrict__ red,
+                                                          const float* __restrict__ partial,
+                                                          uint16_t* __restrict__ dk,
+                                                          uint16_t* __restrict__ dv, int Hkv,
+                                                          float scale) {
+  const KvReduce r = red[blockIdx.x / Hkv];
+  const int g = blockIdx.x % Hkv;
+  const size_t slot_stride = (size_t)Hkv * (2 * kKvTile * kHeadDim);
+  const float* base = partial + ((size_t)r.first_slot * Hkv + g) * (2 * kKvTile * kHeadDim);
+  const int nkeys = r.k1 - r.k0;
+  for (int i = threadIdx.x; i < nkeys * (kHeadDim / 4); i += blockDim.x) {
+    const int key = i / (kHeadDim / 4), d4 = i % (kHeadDim / 4);
+    f32x4 sk = {0.f, 0.f, 0.f, 0.f}, sv = {0.f, 0.f, 0.f, 0.f};
+    for (int p = 0; p < r.nparts; ++p) {
+      const float* src = base + (size_t)p * slot_stride + (size_t)key * kHeadDim + 4 * d4;
+      const f32x4 a = *reinterpret_cast<const f32x4*>(src);
+      const f32x4 b = *reinterpret_cast<const f32x4*>(src + kKvTile * kHeadDim);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { sk[e] += a[e]; sv[e] += b[e]; }
+    }
+    bf16x4 rk, rv;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { rk[e] = (__bf16)(sk[e] * scale); rv[e] = (__bf16)sv[e]; }
+    const size_t o = ((size_t)(r.k0 + key) * Hkv + g) * kHeadDim + 4 * d4;
+    *reinterpret_cast<bf16x4*>(dk + o) = rk;
+    *reinterpret_cast<bf16x4*>(dv + o) = rv;
+  }
+}
+
 }  // namespace
 
 int launch_bwd_bf16(const LaunchArgs& a) {
@@ -347,7 +394,7 @@ int launch_bwd_bf16(const LaunchArgs& a) {
   clear_hip_error();
   const size_t rows = (size_t)a.tree->info.n_tokens * a.p.n_q_heads;
   const size_t qblocks = a.sched->q_tiles.size() * (size_t)a.p.n_kv_heads * (size_t)a.tc.hblocks;
-  const size_t kblocks = a.sched->kv_tiles.size() * (size_t)a.p.n_kv_heads;
+  const size_t kblocks = a.sched->kv_items.size() * (size_t)a.p.n_kv_heads;
   if (qblocks == 0 || qblocks > 0x7fffffffu || kblocks > 0x7fffffffu) return DTA_ERR_UNSUPPORTED;
   if (a.stages & DTA_BWD_DELTA) {
     delta_bf16_kernel<<<(unsigned)((rows + 15) / 16), 256, 0, st>>>(
@@ -363,10 +410,16 @@ int launch_bwd_bf16(const LaunchArgs& a) {
   }
   if (a.stages & DTA_BWD_DKDV) {
     dkdv_bf16_kernel<<<(unsigned)kblocks, kKvThreads, 0, st>>>(
-        a.sched->d_kv_tiles, a.d_kend, (const uint16_t*)a.q, (const uint16_t*)a.k,
+        a.sched->d_kv_items, a.d_kend, (const uint16_t*)a.q, (const uint16_t*)a.k,
         (const uint16_t*)a.v, (const uint16_t*)a.d_o, a.lse_in, a.delta, (uint16_t*)a.dk,
-        (uint16_t*)a.dv, a.p.n_q_heads, a.p.n_kv_heads, a.p.softmax_scale);
+        (uint16_t*)a.dv, a.partial, a.p.n_q_heads, a.p.n_kv_heads, a.p.softmax_scale);
     { int ls = launch_status(__func__); if (ls != DTA_OK) return ls; }
+    if (!a.sched->kv_reduce.empty()) {
+      dkdv_reduce_kernel<<<(unsigned)(a.sched->kv_reduce.size() * a.p.n_kv_heads), 256, 0, st>>>(
+          a.sched->d_kv_reduce, a.partial, (uint16_t*)a.dk, (uint16_t*)a.dv, a.p.n_kv_heads,
+          a.p.softmax_scale);
+      { int ls = launch_status(__func__); if (ls != DTA_OK) return ls; }
+    }
   }
   return DTA_OK;
 }

@@ -38,6 +38,27 @@ struct KvTile {
   int32_t q_full_end;
 };
 
+// One launch unit of the bf16 dK/dV kernel: key tile [k0, k1) and a slice
+// [it_begin, it_end) of its flattened (q head of the group, 64-row query chunk)
+// iteration space.  A tile whose walk is much longer than the average is cut
+// into several items so that no block becomes the critical path; such items
+// write fp32 partial sums to workspace slot `slot` (>= 0) and a reduce launch
+// adds them in a fixed order.  slot < 0: the item covers the whole tile and
+// writes dK/dV directly.
+struct KvItem {
+  int32_t k0, k1;
+  int32_t q_end, q_full_end;
+  int32_t it_begin, it_end;
+  int32_t slot;
+  int32_t pad;
+};
+
+// A split key tile: its partial sums live in slots [first_slot, first_slot + nparts).
+struct KvReduce {
+  int32_t k0, k1;
+  int32_t first_slot, nparts;
+};
+
 // Tile schedule for one (BM, BN) choice: host vectors, and device copies made on
 // first use.  Work items are stored longest first so that the hardware block
 // dispatcher, which hands out blocks in index order, balances the CUs.
@@ -46,12 +67,18 @@ struct Schedule {
   std::vector<QTile> q_tiles;
   std::vector<KeySeg> segs;
   std::vector<KvTile> kv_tiles;
+  int hkv = 0, group = 0;          // head configuration the item split was made for
+  std::vector<KvItem> kv_items;
+  std::vector<KvReduce> kv_reduce;
+  int64_t n_slots = 0;
   int64_t fwd_tile_pairs = 0, bwd_tile_pairs = 0;
   // device copies (owned; freed with the tree)
   int device = -1;
   QTile* d_q_tiles = nullptr;
   KeySeg* d_segs = nullptr;
   KvTile* d_kv_tiles = nullptr;
+  KvItem* d_kv_items = nullptr;
+  KvReduce* d_kv_reduce = nullptr;
 };
 
 }  // namespace dta
@@ -65,8 +92,8 @@ struct dta_tree {
   std::vector<int32_t> token_kend;   // [T]
   std::vector<int32_t> token_node;   // [T] node id owning each packed token
   dta_tree_info_t info{};
-  // schedules keyed by (bm << 16 | bn)
-  std::map<uint32_t, dta::Schedule> schedules;
+  // schedules keyed by (bm, bn, kv heads, group size)
+  std::map<uint64_t, dta::Schedule> schedules;
   int32_t* d_token_kend = nullptr;
   int kend_device = -1;
   std::mutex mu;
@@ -75,7 +102,9 @@ struct dta_tree {
 namespace dta {
 
 // Host: build (or fetch) the schedule for tile sizes (bm, bn).
-Schedule& get_schedule(dta_tree* tree, int bm, int bn);
+Schedule& get_schedule(dta_tree* tree, int bm, int bn, int hkv, int group);
+// Bytes of fp32 partial dK/dV sums the split items of a schedule need.
+size_t partial_bytes(const Schedule& s);
 
 // Tile sizes the kernels use for a head configuration.
 struct TileChoice {
@@ -98,6 +127,7 @@ struct LaunchArgs {
   void *o_out, *dq, *dk, *dv;
   float* lse_out;
   float* delta;  // workspace: D[t,h] = dO.O
+  float* partial;  // workspace: fp32 partial dK/dV of split key tiles
   uint32_t stages;  // backward stages to launch (DTA_BWD_*)
   void* stream;
 };

@@ -148,13 +148,19 @@ namespace dta {
 // tiles, so cutting at node boundaries could only add work.  What a mixed tile
 // must not do is let a row see a key outside its own root path: the kernels
 // mask with kend[] wherever a key interval is not visible to every row.
-Schedule& get_schedule(dta_tree* tree, int bm, int bn) {
-  uint32_t key = ((uint32_t)bm << 16) | (uint32_t)bn;
+size_t partial_bytes(const Schedule& s) {
+  return (size_t)s.n_slots * (size_t)s.hkv * 2u * (size_t)s.bn * 128u * sizeof(float);
+}
+
+Schedule& get_schedule(dta_tree* tree, int bm, int bn, int hkv, int group) {
+  uint64_t key = ((uint64_t)bm << 48) | ((uint64_t)bn << 32) | ((uint64_t)hkv << 16) | (uint64_t)group;
   auto it = tree->schedules.find(key);
   if (it != tree->schedules.end()) return it->second;
   Schedule& s = tree->schedules[key];
   s.bm = bm;
   s.bn = bn;
+  s.hkv = hkv;
+  s.group = group;
   const int64_t T = tree->info.n_tokens;
   const auto& parent = tree->parent;
 
@@ -225,6 +231,41 @@ Schedule& get_schedule(dta_tree* tree, int bm, int bn) {
     sorted.reserve(order.size());
     for (size_t i : order) sorted.push_back(s.kv_tiles[i]);
     s.kv_tiles.swap(sorted);
+  }
+
+  // ---- dK/dV launch items: cut the longest walks so that the chip stays full.
+  // About 2048 equal items per launch keep 256 CUs x 2 resident blocks busy for
+  // four rounds; a tile is cut only when its walk exceeds 1.5x that share.
+  {
+    constexpr int kChunkRows = 64;
+    auto iters_of = [&](const KvTile& t) {
+      return (int64_t)((t.q_end - t.k0 + kChunkRows - 1) / kChunkRows) * group;
+    };
+    int64_t total = 0;
+    for (const KvTile& t : s.kv_tiles) total += iters_of(t);
+    const int64_t target = std::max<int64_t>(32, (total * hkv + 2047) / 2048);
+    std::vector<int64_t> icost;
+    for (const KvTile& t : s.kv_tiles) {
+      const int64_t iters = iters_of(t);
+      int64_t nparts = 1;
+      if (2 * iters > 3 * target) nparts = (iters + target - 1) / target;
+      if (nparts > 1) s.kv_reduce.push_back(KvReduce{t.k0, t.k1, (int32_t)s.n_slots, (int32_t)nparts});
+      for (int64_t p = 0; p < nparts; ++p) {
+        KvItem it{t.k0, t.k1, t.q_end, t.q_full_end, (int32_t)(iters * p / nparts),
+                  (int32_t)(iters * (p + 1) / nparts), nparts > 1 ? (int32_t)(s.n_slots + p) : -1, 0};
+        s.kv_items.push_back(it);
+        icost.push_back(it.it_end - it.it_begin);
+      }
+      if (nparts > 1) s.n_slots += nparts;
+    }
+    std::vector<size_t> order(s.kv_items.size());
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(),
+                     [&](size_t a, size_t b) { return icost[a] > icost[b]; });
+    std::vector<KvItem> sorted;
+    sorted.reserve(order.size());
+    for (size_t i : order) sorted.push_back(s.kv_items[i]);
+    s.kv_items.swap(sorted);
   }
   return s;
 }
@@ -315,12 +356,13 @@ int dta_tree_schedule_info(dta_tree_t* tree, const dta_attn_params_t* params,
   if (st != DTA_OK) return st;
   try {
     std::lock_guard<std::mutex> lock(tree->mu);
-    dta::Schedule& s = dta::get_schedule(tree, tc.bm, tc.bn);
+    dta::Schedule& s = dta::get_schedule(tree, tc.bm, tc.bn, params->n_kv_heads,
+                                         params->n_q_heads / params->n_kv_heads);
     out->fwd_q_tile_tokens = tc.bm;
     out->fwd_work_items = (int64_t)s.q_tiles.size();
     out->fwd_tile_pairs = s.fwd_tile_pairs;
     out->bwd_kv_tile_tokens = tc.bn;
-    out->bwd_work_items = (int64_t)s.kv_tiles.size();
+    out->bwd_work_items = (int64_t)s.kv_items.size();
     out->bwd_tile_pairs = s.bwd_tile_pairs;
   } catch (const std::bad_alloc&) {
     return DTA_ERR_ALLOC;

@@ -102,7 +102,8 @@ def test_config_counts_and_schedule_cover_every_pair():
         tree = dta.tree_build(parent, seg)
         info, sch = tree.info(), tree.schedule_info(p)
         assert sch["fwd_work_items"] == -(-info["n_tokens"] // sch["fwd_q_tile_tokens"])
-        assert sch["bwd_work_items"] == -(-info["n_tokens"] // sch["bwd_kv_tile_tokens"])
+        # long key-tile walks may be cut into several launch items
+        assert sch["bwd_work_items"] >= -(-info["n_tokens"] // sch["bwd_kv_tile_tokens"])
         # a tile streams at least the pairs it owns
         assert sch["fwd_tile_pairs"] >= info["unique_pairs"]
         assert sch["bwd_tile_pairs"] >= info["unique_pairs"]
