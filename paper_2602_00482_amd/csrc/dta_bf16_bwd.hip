@@ -235,14 +235,19 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
     for (int e = 0; e < 16; ++e) { dK[a][e] = 0.f; dV[a][e] = 0.f; }
 
   const size_t q_stride = (size_t)Hq * kHeadDim;
-  // flat iteration over (head of the group, 64-row query chunk); chunk `it` lives
+  // flat iteration over (64-row query chunk, head of the group), heads innermost.
+  // Chunks are walked from the END of the range backwards (reverse DFS order):
+  // key tiles of one node share the end of their query range, and k0 is a
+  // multiple of the chunk size, so blocks that start together read exactly the
+  // same 64-row chunks at the same time and find them in L2.  Step `it` lives
   // in buffer it & 1 and is copied global -> LDS one iteration ahead of its use
   // (this item covers iterations [it_begin, it_end) of the tile's walk)
   const int n_chunks = (tile.q_end - tile.k0 + kBQ - 1) / kBQ;
   const int total = tile.it_end;
   float lse_r = 0.f, dlt_r = 0.f;   // travel through registers, stored a step later
   auto issue = [&](int it, int b) {
-    const int hsub = it / n_chunks, ch = it - hsub * n_chunks;
+    const int cq = it / G, hsub = it - cq * G;
+    const int ch = n_chunks - 1 - cq;
     const int h = g * G + hsub;
     const int r0 = tile.k0 + ch * kBQ;
     const int nv = min(kBQ, tile.q_end - r0);
@@ -263,7 +268,7 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
     if (threadIdx.x < kBQ) { lseS[buf][threadIdx.x] = lse_r; dltS[buf][threadIdx.x] = dlt_r; }
     __syncthreads();   // chunk `buf` has landed; everyone is done with the other buffer
     if (it + 1 < total) issue(it + 1, buf ^ 1);
-    const int ch = it % n_chunks;
+    const int ch = n_chunks - 1 - it / G;
     const int r0 = tile.k0 + ch * kBQ;
     const int nv = min(kBQ, tile.q_end - r0);
     const bool need_mask = !(r0 >= tile.k1 && r0 + kBQ <= tile.q_full_end);

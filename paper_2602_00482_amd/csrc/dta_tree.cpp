@@ -141,6 +141,17 @@ int build_impl(const int32_t* parent, const int32_t* seg_len, int32_t n, dta_tre
 
 namespace dta {
 
+namespace {
+// Work items are launched longest first (the hardware hands out blocks in index
+// order), but only by power-of-two cost class: inside a class the DFS order is
+// kept, so blocks that run at the same time stream neighbouring rows.
+int64_t order_key(int64_t cost) {
+  int64_t b = 0;
+  while ((cost >> b) > 1) ++b;
+  return b;
+}
+}  // namespace
+
 // Both work lists cut the packed token order into fixed runs of bm (bn) tokens,
 // whatever the node boundaries.  A tile pays for all of its padded rows anyway,
 // and the keys (queries) a run of consecutive DFS tokens needs are the union of
@@ -202,7 +213,7 @@ Schedule& get_schedule(dta_tree* tree, int bm, int bn, int hkv, int group) {
     std::vector<size_t> order(s.q_tiles.size());
     std::iota(order.begin(), order.end(), 0);
     std::stable_sort(order.begin(), order.end(),
-                     [&](size_t a, size_t b) { return cost[a] > cost[b]; });
+                     [&](size_t a, size_t b) { return order_key(cost[a]) > order_key(cost[b]); });
     std::vector<QTile> sorted;
     sorted.reserve(order.size());
     for (size_t i : order) sorted.push_back(s.q_tiles[i]);
@@ -226,7 +237,7 @@ Schedule& get_schedule(dta_tree* tree, int bm, int bn, int hkv, int group) {
     std::vector<size_t> order(s.kv_tiles.size());
     std::iota(order.begin(), order.end(), 0);
     std::stable_sort(order.begin(), order.end(),
-                     [&](size_t a, size_t b) { return cost[a] > cost[b]; });
+                     [&](size_t a, size_t b) { return order_key(cost[a]) > order_key(cost[b]); });
     std::vector<KvTile> sorted;
     sorted.reserve(order.size());
     for (size_t i : order) sorted.push_back(s.kv_tiles[i]);
@@ -260,8 +271,13 @@ Schedule& get_schedule(dta_tree* tree, int bm, int bn, int hkv, int group) {
     }
     std::vector<size_t> order(s.kv_items.size());
     std::iota(order.begin(), order.end(), 0);
-    std::stable_sort(order.begin(), order.end(),
-                     [&](size_t a, size_t b) { return icost[a] > icost[b]; });
+    // same cost class: parts that cover the same slice of the walk next to each
+    // other (they stream the same query rows), then DFS order
+    std::stable_sort(order.begin(), order.end(), [&](size_t a, size_t b) {
+      const int64_t ka = order_key(icost[a]), kb = order_key(icost[b]);
+      if (ka != kb) return ka > kb;
+      return s.kv_items[a].it_begin < s.kv_items[b].it_begin;
+    });
     std::vector<KvItem> sorted;
     sorted.reserve(order.size());
     for (size_t i : order) sorted.push_back(s.kv_items[i]);
