@@ -145,23 +145,22 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
         dP = mfma32(va, dOr[ks], dP);
       }
 #pragma unroll
-      for (int e4 = 0; e4 < 4; ++e4) {
-        int kev[4] = {0, 0, 0, 0};
-        if (need_mask) {
-          const int4 ke = *reinterpret_cast<const int4*>(&kendS[buf][32 * mb + 8 * e4 + 4 * hh]);
-          kev[0] = ke.x; kev[1] = ke.y; kev[2] = ke.z; kev[3] = ke.w;
-        }
+      for (int e = 0; e < 16; ++e) S[e] = __builtin_amdgcn_exp2f(fmaf(S[e], sc, -lse2));
+      if (need_mask) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int e = 4 * e4 + j;
-          float p = __builtin_amdgcn_exp2f(fmaf(S[e], sc, -lse2));
-          if (need_mask) {
+        for (int e4 = 0; e4 < 4; ++e4) {
+          const int4 ke = *reinterpret_cast<const int4*>(&kendS[buf][32 * mb + 8 * e4 + 4 * hh]);
+          const int kev[4] = {ke.x, ke.y, ke.z, ke.w};
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const int e = 4 * e4 + j;
             const bool ok = (cc0 + row_of_acc(mb, e, hh) <= qrow) & (qrow < kev[j]);
-            p = ok ? p : 0.f;
+            S[e] = ok ? S[e] : 0.f;
           }
-          S[e] = p * (dP[e] - dlt);
         }
       }
+#pragma unroll
+      for (int e = 0; e < 16; ++e) S[e] *= dP[e] - dlt;
       const bf16x8 dSb0 = pack8(S, 0), dSb1 = pack8(S, 1);
       // dQ^T += K^T dS^T over this 32-key half
 #pragma unroll
@@ -289,6 +288,7 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
         S = mfma32(qa, Kr[ks], S);
         dP = mfma32(da, Vr[ks], dP);
       }
+      __builtin_amdgcn_sched_barrier(0);   // keep the next phase's LDS reads from being hoisted (registers)
 #pragma unroll
       for (int e4 = 0; e4 < 4; ++e4) {
         // accumulator values 4*e4 .. 4*e4+3 are four consecutive matrix positions
@@ -298,19 +298,25 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const int e = 4 * e4 + j;
-          float p = __builtin_amdgcn_exp2f(fmaf(S[e], sc, -ls[j]));
-          if (need_mask) {
-            const int rl = row_of_acc(mq, e, hh);
-            const int t = r0 + rl;
-            const bool ok = (rl < nv) & (kcol <= t) & (t < my_kend);
-            p = ok ? p : 0.f;
-          }
-          S[e] = p;
-          dP[e] = p * (dP[e] - dl[j]);
+          S[e] = __builtin_amdgcn_exp2f(fmaf(S[e], sc, -ls[j]));
+          dP[e] -= dl[j];
         }
       }
+      if (need_mask) {   // query row t sees this lane's key iff kcol <= t < kend[kcol]
+        // row_of_acc(mq, e, hh) = 32*hh + (compile-time part): compare against per-lane bounds
+        const int lo = kcol - r0 - 32 * hh;
+        const int hi = min(my_kend - r0, nv) - 32 * hh;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int rc = row_of_acc(mq, e, 0);
+          S[e] = (rc >= lo) & (rc < hi) ? S[e] : 0.f;
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < 16; ++e) dP[e] *= S[e];
       const bf16x8 Pb0 = pack8(S, 0), Pb1 = pack8(S, 1);
       const bf16x8 dSb0 = pack8(dP, 0), dSb1 = pack8(dP, 1);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int dmb = 0; dmb < 4; ++dmb) {
         const bf16x8 dot0 = tile_col8(dOc, 32 * mq, 32 * dmb);
