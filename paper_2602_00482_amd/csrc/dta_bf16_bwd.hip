@@ -303,9 +303,9 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
         }
       }
       if (need_mask) {   // query row t sees this lane's key iff kcol <= t < kend[kcol]
-        // row_of_acc(mq, e, hh) = 32*hh + (compile-time part): compare against per-lane bounds
-        const int lo = kcol - r0 - 32 * hh;
-        const int hi = min(my_kend - r0, nv) - 32 * hh;
+        // row_of_acc(mq, e, hh) = 4*hh + (compile-time part): compare against per-lane bounds
+        const int lo = kcol - r0 - 4 * hh;
+        const int hi = min(my_kend - r0, nv) - 4 * hh;
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
           const int rc = row_of_acc(mq, e, 0);

@@ -115,20 +115,21 @@ __device__ __forceinline__ void tile_store(const TileRegs<NT>& t, uint16_t* lds)
 // are avoided by choosing WHICH tile row each matrix position uses: the matrix
 // products only need keys (or query rows) to sit at consistent positions, not in
 // order.  Position x (0..63) of a product uses tile row
-//     row_of_pos(x) = 4 * sigma(x & 15) + (x >> 4),  sigma(y) = 2 * (y & 7) + (y >> 3),
+//     row_of_pos(x) = 4 * sigma(x & 15) + (x >> 4),  sigma(y) = 4 * (y & 3) + (y >> 2),
 // and group g starts at g * 1040 bytes.  Then the 16 lanes of one pass of a
 // 16-byte row read touch 16 different groups (16 different 16-byte bank offsets),
-// the 4 rows of one pass of a transposing read sit 32 bytes of bank offset apart,
-// and every read address is a per-lane base plus a compile-time constant.
+// the 4 rows of one pass of a transposing read (32 lanes: 4 rows x 64 bytes) sit
+// 64 bytes of bank offset apart, and every read address is a per-lane base plus
+// a compile-time constant.
 constexpr int kGroupPitch = 4 * kHeadDim + 8;     // elements between 4-row groups (1040 bytes)
 constexpr int kTileElems = 16 * kGroupPitch;      // one 64 x 128 tile
 
-__device__ __forceinline__ int sigma16(int y) { return ((y & 7) << 1) | (y >> 3); }
+__device__ __forceinline__ int sigma16(int y) { return ((y & 3) << 2) | (y >> 2); }
 __device__ __forceinline__ int row_of_pos(int x) { return 4 * sigma16(x & 15) + (x >> 4); }
 // For lane half hh, accumulator value e (0..15) of 32-position block mb holds
 // position 32*mb + 8*(e/4) + 4*hh + e%4, i.e. tile row
 __device__ __forceinline__ int row_of_acc(int mb, int e, int hh) {
-  return 32 * hh + 8 * (e & 3) + 4 * ((e >> 2) & 1) + (e >> 3) + 2 * mb;
+  return 16 * (e & 3) + 8 * ((e >> 2) & 1) + 4 * hh + 2 * mb + (e >> 3);
 }
 
 // Starts the copy of rows [0, 64) x 128 bf16 (global row pitch `stride` elements)
@@ -167,7 +168,7 @@ __device__ __forceinline__ int row_lane_off() {
 }
 // Column operand (contraction over positions r0 .. r0+15, r0 a multiple of 16,
 // columns col0 .. col0+31): same value order as lds_read_col8, at
-//   tile + col_lane_off() + 128 * (r0 / 16) + col0   and   + kGroupPitch for the upper 8
+//   tile + col_lane_off() + 128 * (r0 / 16) + col0   and   + 2 * kGroupPitch for the upper 8
 __device__ __forceinline__ int col_lane_off() {
   const int l = threadIdx.x & 63, i = l & 15, g16 = l >> 4, hh = g16 >> 1;
   return sigma16(4 * hh + (i >> 2)) * kGroupPitch + 16 * (g16 & 1) + 4 * (i & 3);
@@ -178,7 +179,7 @@ __device__ __forceinline__ bf16x8 tile_row8(const uint16_t* lane_ptr, int mb, in
 __device__ __forceinline__ bf16x8 tile_col8(const uint16_t* lane_ptr, int r0, int col0) {
   const uint16_t* p = lane_ptr + kHeadDim * (r0 >> 4) + col0;
   s16x4 lo = lds_read_tr4(p);
-  s16x4 hi = lds_read_tr4(p + kGroupPitch);
+  s16x4 hi = lds_read_tr4(p + 2 * kGroupPitch);
   union {
     struct { s16x4 a, b; } s;
     bf16x8 v;
