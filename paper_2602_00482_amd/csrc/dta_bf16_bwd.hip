@@ -101,6 +101,7 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
   const size_t kv_stride = (size_t)Hkv * kHeadDim;
   const uint16_t* kbase = k + (size_t)g * kHeadDim;
   const uint16_t* vbase = v + (size_t)g * kHeadDim;
+  const uint32_t kv_bytes = (uint32_t)kv_stride * 2;
 
   // chunk i lives in buffer i & 1 and is copied global -> LDS one iteration ahead
   KeyChunks it;
@@ -114,8 +115,8 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
         kendS[b][threadIdx.x] = row >= n ? 0 : (full ? 0x7fffffff : kend[c0 + row]);
       }
     }
-    tile_async_load<kDqThreads>(Ks[b], kbase + (size_t)c0 * kv_stride, kv_stride, n);
-    tile_async_load<kDqThreads>(Vs[b], vbase + (size_t)c0 * kv_stride, kv_stride, n);
+    tile_async_load<kDqThreads>(Ks[b], kbase + (size_t)c0 * kv_stride, kv_bytes, n);
+    tile_async_load<kDqThreads>(Vs[b], vbase + (size_t)c0 * kv_stride, kv_bytes, n);
   };
   issue(0);
   int buf = 0;
@@ -234,6 +235,7 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
     for (int e = 0; e < 16; ++e) { dK[a][e] = 0.f; dV[a][e] = 0.f; }
 
   const size_t q_stride = (size_t)Hq * kHeadDim;
+  const uint32_t q_bytes = (uint32_t)q_stride * 2;
   // flat iteration over (64-row query chunk, head of the group), heads innermost.
   // Chunks are walked from the END of the range backwards (reverse DFS order):
   // key tiles of one node share the end of their query range, and k0 is a
@@ -255,8 +257,8 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
       lse_r = lse[idx] * kLog2e;
       dlt_r = delta[idx];
     }
-    tile_async_load<kKvThreads>(Qs[b], q + (size_t)r0 * q_stride + (size_t)h * kHeadDim, q_stride, nv);
-    tile_async_load<kKvThreads>(dOs[b], d_o + (size_t)r0 * q_stride + (size_t)h * kHeadDim, q_stride, nv);
+    tile_async_load<kKvThreads>(Qs[b], q + (size_t)r0 * q_stride + (size_t)h * kHeadDim, q_bytes, nv);
+    tile_async_load<kKvThreads>(dOs[b], d_o + (size_t)r0 * q_stride + (size_t)h * kHeadDim, q_bytes, nv);
   };
   if (tile.it_begin < total) issue(tile.it_begin, 0);
   int buf = 0;

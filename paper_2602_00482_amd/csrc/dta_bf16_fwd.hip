@@ -69,6 +69,7 @@ __global__ __launch_bounds__(kThreads) void fwd_bf16_kernel(
   const size_t kv_stride = (size_t)Hkv * kHeadDim;
   const uint16_t* kbase = k + (size_t)g * kHeadDim;
   const uint16_t* vbase = v + (size_t)g * kHeadDim;
+  const uint32_t kv_bytes = (uint32_t)kv_stride * 2;
 
   // Chunk i lives in buffer i & 1 and is copied global -> LDS one iteration ahead
   // of its use, so one barrier per chunk is enough.
@@ -83,8 +84,8 @@ __global__ __launch_bounds__(kThreads) void fwd_bf16_kernel(
         kendS[b][threadIdx.x] = row >= n ? 0 : (full ? 0x7fffffff : kend[c0 + row]);
       }
     }
-    tile_async_load<kThreads>(Ks[b], kbase + (size_t)c0 * kv_stride, kv_stride, n);
-    tile_async_load<kThreads>(Vs[b], vbase + (size_t)c0 * kv_stride, kv_stride, n);
+    tile_async_load<kThreads>(Ks[b], kbase + (size_t)c0 * kv_stride, kv_bytes, n);
+    tile_async_load<kThreads>(Vs[b], vbase + (size_t)c0 * kv_stride, kv_bytes, n);
   };
   issue(0);
   int buf = 0;

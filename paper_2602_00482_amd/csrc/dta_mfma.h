@@ -132,27 +132,42 @@ __device__ __forceinline__ int row_of_acc(int mb, int e, int hh) {
   return 16 * (e & 3) + 8 * ((e >> 2) & 1) + 4 * hh + 2 * mb + (e >> 3);
 }
 
-// Starts the copy of rows [0, 64) x 128 bf16 (global row pitch `stride` elements)
-// into `tile`; rows >= nvalid re-read row nvalid-1 (finite data the mask hides).
-// Completion: async_wait_all() by every thread, then a block barrier.
+// Starts the copy of rows [0, 64) x 128 bf16 (global row pitch stride_bytes,
+// `base` uniform over the block) into `tile`; rows >= nvalid re-read row
+// nvalid-1 (finite data the mask hides).  Completion: async_wait_all() by every
+// thread, then a block barrier.
 template <int NT>
-__device__ __forceinline__ void tile_async_load(uint16_t* tile, const uint16_t* base, size_t stride,
-                                                int nvalid) {
+__device__ __forceinline__ void tile_async_load(uint16_t* tile, const uint16_t* base,
+                                                uint32_t stride_bytes, int nvalid) {
   constexpr int NW = NT / 64;
-  const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), l = threadIdx.x & 63;
+  const uint32_t tile_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)tile;
+  // The base is the same for every lane; make that visible so it lands in SGPRs.
+  // (readfirstlane returns a signed int: widen through uint32_t, or a low half
+  // with its top bit set would sign-extend into the high half.)
+  const uint64_t base_bits = (uint64_t)(uintptr_t)base;
+  const uint32_t base_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(base_bits >> 32));
+  const uint32_t base_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)base_bits);
+  const uint64_t sbase = ((uint64_t)base_hi << 32) | (uint64_t)base_lo;
+  // lane part of the address for a full tile: row (l >> 4) of a 4-row group, piece l & 15
+  const uint32_t lane_off = (uint32_t)(l >> 4) * stride_bytes + (l & 15) * 16;
 #pragma unroll
   for (int p = 0; p < 16 / NW; ++p) {
     const int grp = w + NW * p;
-    const int row = 4 * grp + (l >> 4);
-    const uint16_t* g = base + (size_t)min(row, nvalid - 1) * stride + (l & 15) * 8;
+    uint64_t gbase = sbase + (uint64_t)(4 * grp) * stride_bytes;   // scalar
+    uint32_t voff = lane_off;
+    if (nvalid < 64) {   // ragged tail of an interval (uniform branch)
+      gbase = sbase;
+      voff = (uint32_t)min(4 * grp + (l >> 4), nvalid - 1) * stride_bytes + (l & 15) * 16;
+    }
     // Written as inline assembly on purpose: for the builtin form the compiler
     // drains every outstanding load before the next LDS read, which would undo
-    // the prefetch.  LDS destination = M0 + 16 * lane.
-    const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(
-        (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(tile + grp * kGroupPitch));
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
+    // the prefetch.  Address = scalar base + 32-bit lane offset; LDS destination
+    // = M0 + 16 * lane.
+    const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(tile_addr + grp * kGroupPitch * 2);
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
                  :
-                 : "v"(g), "s"(lds_addr)
+                 : "v"(voff), "s"(gbase), "s"(lds_addr)
                  : "memory");
   }
 }
