@@ -311,7 +311,7 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
           const int rc = row_of_acc(mq, e, 0);
-          S[e] = (rc >= lo) & (rc < hi) ? S[e] : 0.f;
+          S[e] = ((rc >= lo) & (rc < hi)) ? S[e] : 0.f;
         }
       }
 #pragma unroll

@@ -1,0 +1,108 @@
+"""GPU tests of the C-ABI behaviour around the kernels: staged backward equals
+the one-call backward, results are bit-reproducible, the split dK/dV path is
+exercised and agrees with the oracle, a negative softmax scale works, and
+run-time argument errors are reported."""
+import ctypes as C
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2602_00482_amd as dta
+from oracle import tree_direct as B
+from workloads import make_inputs_numpy, random_tree
+from parity_util import rel_err, run_hip
+
+pytestmark = pytest.mark.gpu
+
+
+def _setup(parent, seg, Hq, Hkv, d, dtype, seed, scale=None):
+    T = int(np.sum(seg))
+    scale = 1.0 / math.sqrt(d) if scale is None else scale
+    x = make_inputs_numpy(T, Hq, Hkv, d, seed, dtype=dtype)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    t = {n: torch.from_numpy(a).cuda().to(tdt).contiguous() for n, a in x.items()}
+    tree = dta.tree_build(parent, seg)
+    p = dta.AttnParams(Hq, Hkv, d, float(scale), dta.F32 if dtype == "f32" else dta.BF16)
+    return x, t, tree, p, scale
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64)])
+def test_staged_backward_equals_one_call_and_is_reproducible(dtype, d):
+    rng = np.random.default_rng(5)
+    parent, seg = random_tree(rng, 25, 300, n_roots=2)
+    x, t, tree, p, _ = _setup(parent, seg, 8, 2, d, dtype, seed=1)
+    o, lse = dta.tree_attn_fwd(tree, p, t["q"], t["k"], t["v"])
+    o2, lse2 = dta.tree_attn_fwd(tree, p, t["q"], t["k"], t["v"])
+    assert torch.equal(o, o2) and torch.equal(lse, lse2)
+    ref = dta.tree_attn_bwd(tree, p, t["q"], t["k"], t["v"], o, lse, t["do"])
+    again = dta.tree_attn_bwd(tree, p, t["q"], t["k"], t["v"], o, lse, t["do"])
+    for a, b in zip(ref, again):
+        assert torch.equal(a, b)                 # no atomics anywhere: bit-reproducible
+    ws = torch.empty(dta.workspace_bytes(tree, p, True), dtype=torch.uint8, device="cuda")
+    dq, dk, dv = (torch.full_like(a, float("nan")) for a in ref)
+    args = (tree, p, t["q"], t["k"], t["v"], o, lse, t["do"], dq, dk, dv, ws)
+    dta.tree_attn_bwd(*args, stages=dta.BWD_DELTA)
+    dta.tree_attn_bwd(*args, stages=dta.BWD_DKDV)
+    assert torch.isnan(dq).all()                 # stages that were not asked for leave their outputs alone
+    dta.tree_attn_bwd(*args, stages=dta.BWD_DQ)
+    torch.cuda.synchronize()
+    for a, b in zip(ref, (dq, dk, dv)):
+        assert torch.equal(a, b)
+    tree.destroy()
+
+
+def test_split_key_tiles_are_exercised_and_correct():
+    """One long root whose key tiles have much longer walks than the leaves':
+    the schedule must cut them, and the reduced result must match the oracle."""
+    parent = np.array([-1] + [0] * 6, dtype=np.int32)
+    seg = np.array([700, 90, 33, 260, 64, 129, 17], dtype=np.int32)
+    tree = dta.tree_build(parent, seg)
+    p = dta.AttnParams(8, 2, 128, 0.088, dta.BF16)
+    sch = tree.schedule_info(p)
+    assert sch["bwd_work_items"] > -(-int(seg.sum()) // sch["bwd_kv_tile_tokens"])
+    assert dta.workspace_bytes(tree, p, True) > int(seg.sum()) * 8 * 4 + 256
+    tree.destroy()
+    T = int(seg.sum())
+    x = make_inputs_numpy(T, 8, 2, 128, 3, dtype="bf16")
+    got = run_hip(parent, seg, x, 8, 2, 128, 0.088, "bf16")
+    dQ, dK, dV = B.backward(parent, seg, x["q"], x["k"], x["v"], x["do"], 0.088)
+    assert rel_err(got["dq"], dQ) <= 1e-2 and rel_err(got["dk"], dK) <= 1e-2 and rel_err(got["dv"], dV) <= 1e-2
+
+
+@pytest.mark.parametrize("dtype,d,tol", [("bf16", 128, 1e-2), ("f32", 128, 1e-5)])
+def test_negative_and_large_scale(dtype, d, tol):
+    rng = np.random.default_rng(9)
+    parent, seg = random_tree(rng, 12, 150)
+    T = int(seg.sum())
+    for scale in (-0.05, 0.3):
+        x = make_inputs_numpy(T, 4, 2, d, 4, dtype=dtype)
+        got = run_hip(parent, seg, x, 4, 2, d, scale, dtype)
+        O, LSE = B.forward(parent, seg, x["q"], x["k"], x["v"], scale)
+        dQ, dK, dV = B.backward(parent, seg, x["q"], x["k"], x["v"], x["do"], scale)
+        for name, ref in (("o", O), ("lse", LSE), ("dq", dQ), ("dk", dK), ("dv", dV)):
+            assert rel_err(got[name], ref) <= tol, (scale, name)
+
+
+def test_runtime_argument_errors():
+    parent, seg = np.array([-1, 0], dtype=np.int32), np.array([40, 30], dtype=np.int32)
+    x, t, tree, p, _ = _setup(parent, seg, 4, 2, 128, "bf16", seed=2)
+    o, lse = dta.tree_attn_fwd(tree, p, t["q"], t["k"], t["v"])
+    lib = dta.load_library()
+    ptr = lambda a: C.c_void_p(a.data_ptr())
+    z = C.c_void_p(0)
+    need = dta.workspace_bytes(tree, p, True)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    dq, dk, dv = torch.empty_like(t["q"]), torch.empty_like(t["k"]), torch.empty_like(t["v"])
+    base = [tree.handle, C.byref(p), ptr(t["q"]), ptr(t["k"]), ptr(t["v"]), ptr(o), ptr(lse), ptr(t["do"]),
+            ptr(dq), ptr(dk), ptr(dv)]
+    assert lib.dta_tree_attn_bwd(*base, ptr(ws), need - 1, z) == -6          # workspace too small
+    assert lib.dta_tree_attn_bwd(*base, z, need, z) == -6                    # workspace null
+    assert lib.dta_tree_attn_bwd(*base, C.c_void_p(ws.data_ptr() + 16), need, z) == -6   # not 256-aligned
+    mis = C.c_void_p(t["q"].data_ptr() + 2)
+    assert lib.dta_tree_attn_fwd(tree.handle, C.byref(p), mis, ptr(t["k"]), ptr(t["v"]), ptr(o), ptr(lse),
+                                 z, 0, z) == -1                              # misaligned tensor
+    assert lib.dta_tree_attn_bwd(*base, ptr(ws), need, z) == 0
+    torch.cuda.synchronize()
+    tree.destroy()

@@ -1,0 +1,144 @@
+"""GPU parity at the benchmark's full sizes (configurations 2-5, bf16), in the
+launch configuration bench.py times.  The fp64 oracle cannot cover whole tensors
+here, so it is run on sampled outputs it can compute one by one:
+
+  * O, LSE and dQ rows of sampled nodes (tree-direct oracle, every q head of one
+    kv group; a node's rows depend only on its own root path);
+  * dK, dV rows of a sampled subtree's nodes: every query that sees those keys
+    lies inside the subtree, so the oracle restricted to the subtree's queries is
+    complete for them;
+and on properties that hold at any size:
+  * sum_k dV[k, g] == sum over the group's q heads and all tokens of dO (rows of P
+    sum to one), per kv head and feature;
+  * sum_t q_t . dQ_t == sum_k k_k . dK_k per kv group (scores are bilinear);
+  * token 0 of every root sees only itself: O = V, LSE = scale * q.k.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2602_00482_amd as dta
+from oracle import tree_direct as B
+from oracle import tree_layout as L
+from workloads import config_heads, config_tree
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-2
+
+
+def _run(cfg):
+    parent, seg, meta = config_tree(cfg)
+    h = config_heads(cfg)
+    Hq, Hkv, d = h["n_q_heads"], h["n_kv_heads"], h["head_dim"]
+    T = int(seg.sum())
+    g = torch.Generator(device="cuda")
+    g.manual_seed(meta["tensor_seed"])
+    mk = lambda heads: torch.randn((T, heads, d), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    q, k, v, do = mk(Hq), mk(Hkv), mk(Hkv), mk(Hq)
+    scale = 1.0 / math.sqrt(d)
+    p = dta.AttnParams(Hq, Hkv, d, scale, dta.BF16)
+    tree = dta.tree_build(parent, seg)
+    o, lse = dta.tree_attn_fwd(tree, p, q, k, v)
+    dq, dk, dv = dta.tree_attn_bwd(tree, p, q, k, v, o, lse, do)
+    torch.cuda.synchronize()
+    tree.destroy()
+    return parent, seg, (Hq, Hkv, d, scale), dict(q=q, k=k, v=v, do=do, o=o, lse=lse, dq=dq, dk=dk, dv=dv)
+
+
+def _rel(got, ref):
+    return float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-30))
+
+
+def _subtree_nodes(parent, root):
+    kids = {}
+    for i, pa in enumerate(parent):
+        kids.setdefault(int(pa), []).append(i)
+    out, stack = [], [root]
+    while stack:
+        u = stack.pop()
+        out.append(u)
+        stack.extend(kids.get(u, []))
+    return out
+
+
+@pytest.mark.parametrize("cfg", [2, 3, 4, 5])
+def test_full_size_sampled_rows_and_invariants(cfg):
+    parent, seg, (Hq, Hkv, d, scale), t = _run(cfg)
+    G = Hq // Hkv
+    T = int(seg.sum())
+    off, _ = L.node_offsets(parent, seg)
+    sd = L.start_depths(parent, seg)
+    rng = np.random.default_rng(cfg)
+    grp = int(rng.integers(0, Hkv))                    # one whole kv group
+    heads = list(range(grp * G, (grp + 1) * G))
+
+    # ---------------- properties over whole tensors
+    dv_sum = t["dv"].double().sum(dim=0).cpu().numpy()                               # [Hkv, d]
+    do_sum = t["do"].double().view(T, Hkv, G, d).sum(dim=(0, 2)).cpu().numpy()
+    assert np.abs(dv_sum - do_sum).max() / np.abs(do_sum).max() < TOL
+    lhs = (t["q"].double() * t["dq"].double()).sum(dim=(0, 2)).view(Hkv, G).sum(dim=1).cpu().numpy()
+    rhs = (t["k"].double() * t["dk"].double()).sum(dim=(0, 2)).cpu().numpy()
+    assert np.abs(lhs - rhs).max() / max(np.abs(lhs).max(), np.abs(rhs).max()) < 2 * TOL
+    for r in np.flatnonzero(parent < 0)[:8]:
+        t0 = int(off[r])
+        assert torch.equal(t["o"][t0].view(Hkv, G, d), t["v"][t0].unsqueeze(1).expand(Hkv, G, d))
+        s0 = scale * (t["q"][t0].double().view(Hkv, G, d) * t["k"][t0].double().unsqueeze(1)).sum(-1)
+        assert (t["lse"][t0].double().view(Hkv, G) - s0).abs().max().item() < 1e-4
+
+    # ---------------- the oracle on slices: only the tokens it touches are copied to the host
+    def oracle_on(nodes_for_queries):
+        """Run the tree-direct oracle for the queries of these nodes on a compact
+        copy of the tokens involved (their root paths)."""
+        need = set()
+        for u in nodes_for_queries:
+            need.update(L.node_path(parent, u))
+        keep = sorted(need, key=lambda u: off[u])
+        remap = {u: i for i, u in enumerate(keep)}
+        sub_parent = np.array([-1 if parent[u] < 0 else remap[int(parent[u])] for u in keep], dtype=np.int32)
+        sub_seg = np.array([seg[u] for u in keep], dtype=np.int32)
+        tok = np.concatenate([np.arange(off[u], off[u] + seg[u]) for u in keep])
+        ti = torch.from_numpy(tok).cuda()
+        sub = {n: t[n][ti][:, heads if n in ("q", "do") else [grp]].double().cpu().numpy() for n in ("q", "k", "v", "do")}
+        qn = [remap[u] for u in nodes_for_queries]
+        O, LSE = B.forward(sub_parent, sub_seg, sub["q"], sub["k"], sub["v"], scale, nodes=qn)
+        dQ, dK, dV = B.backward(sub_parent, sub_seg, sub["q"], sub["k"], sub["v"], sub["do"], scale, nodes=qn)
+        sub_off, _ = L.node_offsets(sub_parent, sub_seg)
+        return keep, remap, sub_off, tok, O, LSE, dQ, dK, dV
+
+    # (1) O, LSE, dQ on sampled nodes (deepest leaf, a random leaf, a random interior node)
+    leaves = L.leaves(parent)
+    deepest = max(leaves, key=lambda u: sd[u] + seg[u])
+    picks = {deepest, int(rng.choice(leaves)), int(rng.integers(0, len(parent)))}
+    for u in picks:
+        keep, remap, sub_off, tok, O, LSE, dQ, _, _ = oracle_on([u])
+        rows_sub = np.arange(sub_off[remap[u]], sub_off[remap[u]] + seg[u])
+        rows = torch.from_numpy(tok[rows_sub]).cuda()
+        got_o = t["o"][rows][:, heads].double().cpu().numpy()
+        got_l = t["lse"][rows][:, heads].double().cpu().numpy()
+        got_dq = t["dq"][rows][:, heads].double().cpu().numpy()
+        eo, el, eq = _rel(got_o, O[rows_sub]), _rel(got_l, LSE[rows_sub]), _rel(got_dq, dQ[rows_sub])
+        print(f"cfg{cfg} node {u} (len {seg[u]}, depth {sd[u]}): o={eo:.2e} lse={el:.2e} dq={eq:.2e}", flush=True)
+        assert eo <= TOL and el <= TOL and eq <= TOL
+
+    # (2) dK, dV inside a sampled subtree of affordable size
+    sub_tok = {u: sum(int(seg[x]) for x in _subtree_nodes(parent, u)) for u in range(len(parent))} \
+        if len(parent) <= 600 else None
+    cands = [u for u in range(len(parent)) if parent[u] >= 0]
+    if sub_tok is None:
+        cands = [int(x) for x in rng.choice(cands, size=200, replace=False)]
+        sub_tok = {u: sum(int(seg[x]) for x in _subtree_nodes(parent, u)) for u in cands}
+    cands = [u for u in cands if 1 < len(_subtree_nodes(parent, u)) and sub_tok[u] <= 6000] or \
+            [u for u in cands if sub_tok[u] <= 6000]
+    root = max(cands, key=lambda u: sub_tok[u])
+    nodes = _subtree_nodes(parent, root)
+    keep, remap, sub_off, tok, _, _, _, dK, dV = oracle_on(nodes)
+    rows_sub = np.concatenate([np.arange(sub_off[remap[u]], sub_off[remap[u]] + seg[u]) for u in nodes])
+    rows = torch.from_numpy(tok[rows_sub]).cuda()
+    got_dk = t["dk"][rows][:, [grp]].double().cpu().numpy()
+    got_dv = t["dv"][rows][:, [grp]].double().cpu().numpy()
+    ek, ev = _rel(got_dk, dK[rows_sub]), _rel(got_dv, dV[rows_sub])
+    print(f"cfg{cfg} subtree of node {root}: {len(nodes)} nodes, {len(rows_sub)} keys: dk={ek:.2e} dv={ev:.2e}", flush=True)
+    assert ek <= TOL and ev <= TOL
