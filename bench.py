@@ -37,6 +37,12 @@ WORKLOAD_NAMES = {
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 # flop per unique pair per q head, in units of head_dim, that each launch must do
 KERNEL_FLOP_D = {"fwd": 4, "dq": 6, "dkdv": 8}
+# HBM bytes per launch (read + written) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+# this workload, each counter scaled by what it reads for a plain 1 GiB copy (FETCH_SIZE x2.000,
+# WRITE_SIZE x1.000); see profiles/cfg2_grpo_tree_hbm_traffic.md.  Not measured live.
+MEASURED_TRAFFIC_BYTES = {
+    "cfg2_grpo_single_prompt_tree": {"fwd": 4.57e8, "dq": 6.50e8, "dkdv": 3.52e9},
+}
 
 
 def _device_inputs(T, Hq, Hkv, d, seed, dtype):
@@ -266,7 +272,8 @@ def main():
         "config": {k: main_res[k] for k in ("workload", "n_tokens", "n_nodes", "n_leaves", "max_path_tokens",
                                             "unique_pairs", "heads", "head_dim", "tree_seed", "tensor_seed")},
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                     "frac": achieved / peak, "traffic": None,
+                     "frac": achieved / peak,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(main_res["workload"], {}).get(dom),
                      "flop_per_pair_per_head": KERNEL_FLOP_D[dom] * d, "avg_launch_ms": kern[dom]},
         "cpu_baseline": cpu,
         "detail": main_res,
