@@ -89,7 +89,7 @@ typedef struct {
   int32_t n_q_heads;
   int32_t n_kv_heads;   /* must divide n_q_heads; q head h uses kv head h / (n_q_heads/n_kv_heads) */
   int32_t head_dim;     /* 64 or 128 (DTA_F32), 128 (DTA_BF16)                                     */
-  float softmax_scale;  /* multiplies q.k before the softmax                                       */
+  float softmax_scale;  /* multiplies q.k before the softmax; finite and nonzero, else INVALID_ARG   */
   int32_t dtype;        /* DTA_F32 or DTA_BF16: element type of q,k,v,o,dO,dq,dk,dv                */
 } dta_attn_params_t;
 

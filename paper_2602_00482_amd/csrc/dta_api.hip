@@ -15,11 +15,12 @@ size_t delta_bytes(const dta_tree* tree, const dta_attn_params_t* p) {
   return round_up((size_t)tree->info.n_tokens * (size_t)p->n_q_heads * sizeof(float), 256);
 }
 
-// delta plus, in bf16 mode, the partial sums of split key tiles (building the
+// delta plus, in bf16 mode, the rescaled lse and the partial sums of split key tiles (building the
 // host schedule if this head configuration has not been seen yet)
 size_t bwd_workspace_bytes(dta_tree* tree, const dta::TileChoice& tc, const dta_attn_params_t* p) {
   size_t bytes = delta_bytes(tree, p);
   if (p->dtype == DTA_BF16) {
+    bytes += delta_bytes(tree, p);   // lse in log2 units, same shape as delta
     try {
       std::lock_guard<std::mutex> lock(tree->mu);
       bytes += dta::partial_bytes(
@@ -204,7 +205,8 @@ int dta_tree_attn_bwd_stages(dta_tree_t* tree, const dta_attn_params_t* params, 
   a.dk = dk;
   a.dv = dv;
   a.delta = (float*)workspace;
-  a.partial = (float*)((char*)workspace + delta_bytes(tree, params));
+  a.lse2 = (float*)((char*)workspace + delta_bytes(tree, params));
+  a.partial = (float*)((char*)workspace + 2 * delta_bytes(tree, params));
   a.stages = stage_mask;
   a.stream = hip_stream;
   return params->dtype == DTA_F32 ? dta::launch_bwd_f32(a) : dta::launch_bwd_bf16(a);

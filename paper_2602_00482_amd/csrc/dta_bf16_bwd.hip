@@ -16,6 +16,8 @@
 // must be read along tile rows come from the transposing LDS read.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "dta_internal.h"
 #include "dta_mfma.h"
 #include "dta_tile_walk.h"
@@ -32,7 +34,10 @@ __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) {
 // 16 lanes per (token, head) row, 8 elements each.
 __global__ __launch_bounds__(256) void delta_bf16_kernel(const uint16_t* __restrict__ o,
                                                          const uint16_t* __restrict__ d_o,
-                                                         float* __restrict__ delta, size_t rows) {
+                                                         const float* __restrict__ lse,
+                                                         float* __restrict__ neg_delta,
+                                                         float* __restrict__ neg_lse_s,
+                                                         float inv_scale, size_t rows) {
   const size_t row = (size_t)blockIdx.x * 16 + (threadIdx.x >> 4);
   const int j = threadIdx.x & 15;
   float s = 0.f;
@@ -50,7 +55,13 @@ __global__ __launch_bounds__(256) void delta_bf16_kernel(const uint16_t* __restr
   s += __shfl_xor(s, 2);
   s += __shfl_xor(s, 4);
   s += __shfl_xor(s, 8);
-  if (row < rows && j == 0) delta[row] = s;
+  // Stored negated, and lse divided by the softmax scale: the dK/dV kernel
+  // starts its score and dP accumulators from these values, so that
+  // P = exp(scale * acc) and dS = P * acc need no further subtraction.
+  if (row < rows && j == 0) {
+    neg_delta[row] = -s;
+    neg_lse_s[row] = -lse[row] * inv_scale;
+  }
 }
 
 constexpr int kDqThreads = 512;
@@ -62,7 +73,7 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
     const int32_t* __restrict__ kend, const uint16_t* __restrict__ q,
     const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const uint16_t* __restrict__ d_o, const float* __restrict__ lse,
-    const float* __restrict__ delta, uint16_t* __restrict__ dq, int Hq, int Hkv, int HB,
+    const float* __restrict__ neg_delta, uint16_t* __restrict__ dq, int Hq, int Hkv, int HB,
     int hblocks, float scale) {
   __shared__ __attribute__((aligned(1024))) uint16_t Ks[2][kTileElems];
   __shared__ __attribute__((aligned(1024))) uint16_t Vs[2][kTileElems];
@@ -90,7 +101,7 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
       dOr[ks] = *reinterpret_cast<const bf16x8*>(dop + 16 * ks);
     }
   }
-  const float lse2 = lse[rh] * kLog2e, dlt = delta[rh];
+  const float lse2 = lse[rh] * kLog2e, ndlt = neg_delta[rh];
 
   f32x16 dQ[4];
 #pragma unroll
@@ -161,7 +172,7 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
         }
       }
 #pragma unroll
-      for (int e = 0; e < 16; ++e) S[e] *= dP[e] - dlt;
+      for (int e = 0; e < 16; ++e) S[e] *= dP[e] + ndlt;
       const bf16x8 dSb0 = pack8(S, 0), dSb1 = pack8(S, 1);
       // dQ^T += K^T dS^T over this 32-key half
 #pragma unroll
@@ -200,12 +211,26 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
     const KvItem* __restrict__ items, const int32_t* __restrict__ kend,
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, const uint16_t* __restrict__ d_o,
-    const float* __restrict__ lse, const float* __restrict__ delta, uint16_t* __restrict__ dk,
-    uint16_t* __restrict__ dv, float* __restrict__ partial, int Hq, int Hkv, float scale) {
-  __shared__ __attribute__((aligned(1024))) uint16_t Qs[2][kTileElems];
-  __shared__ __attribute__((aligned(1024))) uint16_t dOs[2][kTileElems];
-  __shared__ __attribute__((aligned(16))) float lseS[2][kBQ];
-  __shared__ __attribute__((aligned(16))) float dltS[2][kBQ];
+    const float* __restrict__ neg_lse_s, const float* __restrict__ neg_delta,
+    uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, float* __restrict__ partial, int Hq,
+    int Hkv, float scale) {
+  // One object, so that every tile read is "per-lane base + compile-time offset".
+  // The last k-steps of this wave's K and V operands (kStashK and kStashV of the
+  // 8) live in LDS instead of registers, and so do the per-lane mask bounds
+  // (key position, end of its visibility): with all of them in registers the
+  // kernel needs a few more than 256, and the compiler's scratch reloads (vector
+  // memory) would wait for, i.e. serialise, the tile copies in flight.  Each lane
+  // reads back only what it wrote itself.
+  constexpr int kStashK = 1, kStashV = 2;
+  constexpr int kRegK = 8 - kStashK, kRegV = 8 - kStashV;
+  struct Smem {
+    uint16_t Q[2][kTileElems];
+    uint16_t dO[2][kTileElems];
+    float stat[2][2][kBQ];   // [buffer][-lse/scale | -delta][position]
+    uint16_t stash[4][kStashK + kStashV][64 * 8];
+    int2 bound[kKvThreads];
+  };
+  __shared__ __attribute__((aligned(256))) Smem sm;
 
   const KvItem tile = items[blockIdx.x / Hkv];
   const int g = blockIdx.x % Hkv;
@@ -218,14 +243,26 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
   const int kcol = tile.k0 + 32 * w + c;
   const int kc = min(kcol, tile.k1 - 1);
   const int my_kend = kcol < tile.k1 ? kend[kc] : 0;   // padded columns see nothing
-  bf16x8 Kr[8], Vr[8];
+  sm.bound[threadIdx.x] = make_int2(kcol, my_kend);
+  // rows [wave_lo, wave_hi) are the only ones any of this wave's 32 keys can see
+  int wave_hi = my_kend;
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) wave_hi = max(wave_hi, __shfl_xor(wave_hi, off));
+  wave_hi = __builtin_amdgcn_readfirstlane(wave_hi);
+  const int wave_lo = tile.k0 + 32 * __builtin_amdgcn_readfirstlane(w);
+  bf16x8 Kr[kRegK], Vr[kRegV];
+  uint16_t* stash = &sm.stash[w][0][l * 8];
   {
     const uint16_t* kp = k + ((size_t)kc * Hkv + g) * kHeadDim + 8 * hh;
     const uint16_t* vp = v + ((size_t)kc * Hkv + g) * kHeadDim + 8 * hh;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-      Kr[ks] = *reinterpret_cast<const bf16x8*>(kp + 16 * ks);
-      Vr[ks] = *reinterpret_cast<const bf16x8*>(vp + 16 * ks);
+      const bf16x8 kx = *reinterpret_cast<const bf16x8*>(kp + 16 * ks);
+      const bf16x8 vx = *reinterpret_cast<const bf16x8*>(vp + 16 * ks);
+      if (ks < kRegK) Kr[ks < kRegK ? ks : 0] = kx;
+      else *reinterpret_cast<bf16x8*>(stash + (ks - kRegK) * 512) = kx;
+      if (ks < kRegV) Vr[ks < kRegV ? ks : 0] = vx;
+      else *reinterpret_cast<bf16x8*>(stash + (kStashK + ks - kRegV) * 512) = vx;
     }
   }
   f32x16 dK[4], dV[4];
@@ -245,69 +282,93 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
   // (this item covers iterations [it_begin, it_end) of the tile's walk)
   const int n_chunks = (tile.q_end - tile.k0 + kBQ - 1) / kBQ;
   const int total = tile.it_end;
-  float lse_r = 0.f, dlt_r = 0.f;   // travel through registers, stored a step later
   auto issue = [&](int it, int b) {
     const int cq = it / G, hsub = it - cq * G;
     const int ch = n_chunks - 1 - cq;
     const int h = g * G + hsub;
     const int r0 = tile.k0 + ch * kBQ;
     const int nv = min(kBQ, tile.q_end - r0);
-    if (threadIdx.x < kBQ) {   // lseS / dltS are indexed by matrix position
-      const size_t idx = (size_t)min(r0 + row_of_pos(threadIdx.x), tile.q_end - 1) * Hq + h;
-      lse_r = lse[idx] * kLog2e;
-      dlt_r = delta[idx];
+    if (__builtin_amdgcn_readfirstlane(w) == 0) {   // stat is indexed by matrix position
+      const uint32_t off = (uint32_t)min(row_of_pos(l), nv - 1) * (uint32_t)Hq;
+      row_async_load(sm.stat[b][0], neg_lse_s + (size_t)r0 * Hq + h, off);
+      row_async_load(sm.stat[b][1], neg_delta + (size_t)r0 * Hq + h, off);
     }
-    tile_async_load<kKvThreads>(Qs[b], q + (size_t)r0 * q_stride + (size_t)h * kHeadDim, q_bytes, nv);
-    tile_async_load<kKvThreads>(dOs[b], d_o + (size_t)r0 * q_stride + (size_t)h * kHeadDim, q_bytes, nv);
+    tile_async_load<kKvThreads>(sm.Q[b], q + (size_t)r0 * q_stride + (size_t)h * kHeadDim, q_bytes, nv);
+    tile_async_load<kKvThreads>(sm.dO[b], d_o + (size_t)r0 * q_stride + (size_t)h * kHeadDim, q_bytes, nv);
   };
   if (tile.it_begin < total) issue(tile.it_begin, 0);
-  int buf = 0;
   const int rlo = row_lane_off(), clo = col_lane_off();
 
-  for (int it = tile.it_begin; it < total; ++it) {
+  // one step of the walk; the buffer index is a compile-time constant
+  auto step = [&](int it, auto buf_c) {
+    constexpr int buf = decltype(buf_c)::value;
     async_wait_all();
-    if (threadIdx.x < kBQ) { lseS[buf][threadIdx.x] = lse_r; dltS[buf][threadIdx.x] = dlt_r; }
     __syncthreads();   // chunk `buf` has landed; everyone is done with the other buffer
     if (it + 1 < total) issue(it + 1, buf ^ 1);
     const int ch = n_chunks - 1 - it / G;
     const int r0 = tile.k0 + ch * kBQ;
     const int nv = min(kBQ, tile.q_end - r0);
     const bool need_mask = !(r0 >= tile.k1 && r0 + kBQ <= tile.q_full_end);
-    const uint16_t* Qt = Qs[buf] + rlo;
-    const uint16_t* dOt = dOs[buf] + rlo;
-    const uint16_t* Qc = Qs[buf] + clo;
-    const uint16_t* dOc = dOs[buf] + clo;
+    const uint16_t* Qt = sm.Q[buf] + rlo;
+    const uint16_t* dOt = sm.dO[buf] + rlo;
+    const uint16_t* Qc = sm.Q[buf] + clo;
+    const uint16_t* dOc = sm.dO[buf] + clo;
 
+    // Small per-lane LDS addresses are recomputed every step from a value the
+    // compiler cannot see through: kept across the loop they would be spilled,
+    // and a reload from scratch waits for the copies just issued.
+    int tid_now = threadIdx.x;
+    asm volatile("" : "+v"(tid_now));
+    const float* stat = &sm.stat[buf][0][4 * ((tid_now >> 5) & 1)];
+    // a chunk none of this wave's keys can see contributes nothing (wave-uniform)
+    const bool wave_sees = r0 + nv > wave_lo && r0 < wave_hi;
 #pragma unroll
     for (int mq = 0; mq < 2; ++mq) {
+      if (!wave_sees) continue;
+      // accumulators start from -lse/scale and -delta of their rows (values
+      // 4*e4 .. 4*e4+3 of a lane are four consecutive matrix positions)
       f32x16 S, dP;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) { S[e] = 0.f; dP[e] = 0.f; }
+      for (int e4 = 0; e4 < 4; ++e4) {
+        const f32x4 ls = *reinterpret_cast<const f32x4*>(stat + (32 * mq + 8 * e4));
+        const f32x4 dl = *reinterpret_cast<const f32x4*>(stat + (kBQ + 32 * mq + 8 * e4));
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { S[4 * e4 + j] = ls[j]; dP[4 * e4 + j] = dl[j]; }
+      }
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
         const bf16x8 qa = tile_row8(Qt, mq, ks);
         const bf16x8 da = tile_row8(dOt, mq, ks);
-        S = mfma32(qa, Kr[ks], S);
-        dP = mfma32(da, Vr[ks], dP);
+        const bf16x8 kb = ks < kRegK ? Kr[ks < kRegK ? ks : 0]
+                                     : *reinterpret_cast<const bf16x8*>(stash + (ks - kRegK) * 512);
+        const bf16x8 vb = ks < kRegV ? Vr[ks < kRegV ? ks : 0]
+                                     : *reinterpret_cast<const bf16x8*>(stash + (kStashK + ks - kRegV) * 512);
+        S = mfma32(qa, kb, S);
+        dP = mfma32(da, vb, dP);
       }
-      __builtin_amdgcn_sched_barrier(0);   // keep the next phase's LDS reads from being hoisted (registers)
+      // Fixed software pipeline for this phase: operand reads run two k-steps
+      // ahead of the matrix products and no further, which bounds the registers
+      // the reads in flight can take (0x100 = LDS read, 0x008 = MFMA).
+      __builtin_amdgcn_sched_group_barrier(0x100, 8 + 4, 0);
 #pragma unroll
-      for (int e4 = 0; e4 < 4; ++e4) {
-        // accumulator values 4*e4 .. 4*e4+3 are four consecutive matrix positions
-        const int rl0 = 32 * mq + 8 * e4 + 4 * hh;
-        const f32x4 ls = *reinterpret_cast<const f32x4*>(&lseS[buf][rl0]);
-        const f32x4 dl = *reinterpret_cast<const f32x4*>(&dltS[buf][rl0]);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int e = 4 * e4 + j;
-          S[e] = __builtin_amdgcn_exp2f(fmaf(S[e], sc, -ls[j]));
-          dP[e] -= dl[j];
-        }
+      for (int i = 0; i < 4; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
       }
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2 + (kStashK > 1) + (kStashV > 1), 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2 + (kStashK > 0) + (kStashV > 0), 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      __builtin_amdgcn_sched_barrier(0);   // the next phase's LDS reads stay behind this point
+#pragma unroll
+      for (int e = 0; e < 16; ++e) S[e] = __builtin_amdgcn_exp2f(S[e] * sc);
       if (need_mask) {   // query row t sees this lane's key iff kcol <= t < kend[kcol]
         // row_of_acc(mq, e, hh) = 4*hh + (compile-time part): compare against per-lane bounds
-        const int lo = kcol - r0 - 4 * hh;
-        const int hi = min(my_kend - r0, nv) - 4 * hh;
+        const int2 bnd = sm.bound[tid_now];
+        const int lo = bnd.x - r0 - 4 * hh;
+        const int hi = min(bnd.y - r0, nv) - 4 * hh;
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
           const int rc = row_of_acc(mq, e, 0);
@@ -333,8 +394,21 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
         dK[dmb] = mfma32(qt0, dSb0, dK[dmb]);
         dK[dmb] = mfma32(qt1, dSb1, dK[dmb]);
       }
+      // same idea: the transposing reads run kTrAhead matrix products ahead
+      constexpr int kTrAhead = 3;
+      __builtin_amdgcn_sched_group_barrier(0x100, 2 * kTrAhead, 0);
+#pragma unroll
+      for (int i = 0; i < 16 - kTrAhead; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, kTrAhead, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    buf ^= 1;
+  };
+  for (int it = tile.it_begin; it < total; it += 2) {
+    step(it, std::integral_constant<int, 0>{});
+    if (it + 1 < total) step(it + 1, std::integral_constant<int, 1>{});
   }
 
   if (tile.slot >= 0) {
@@ -376,12 +450,15 @@ __global__ __launch_bounds__(256) void dkdv_reduce_kernel(const KvReduce* __rest
                                                           uint16_t* __restrict__ dk,
                                                           uint16_t* __restrict__ dv, int Hkv,
                                                           float scale) {
-  const KvReduce r = red[blockIdx.x / Hkv];
-  const int g = blockIdx.x % Hkv;
+  // 8 blocks per (tile, kv head), 16 keys each, so that even a handful of split
+  // tiles fills the chip
+  const int sub = blockIdx.x & 7;
+  const KvReduce r = red[(blockIdx.x >> 3) / Hkv];
+  const int g = (blockIdx.x >> 3) % Hkv;
   const size_t slot_stride = (size_t)Hkv * (2 * kKvTile * kHeadDim);
   const float* base = partial + ((size_t)r.first_slot * Hkv + g) * (2 * kKvTile * kHeadDim);
-  const int nkeys = r.k1 - r.k0;
-  for (int i = threadIdx.x; i < nkeys * (kHeadDim / 4); i += blockDim.x) {
+  const int key_lo = sub * (kKvTile / 8), key_hi = min(r.k1 - r.k0, key_lo + kKvTile / 8);
+  for (int i = key_lo * (kHeadDim / 4) + threadIdx.x; i < key_hi * (kHeadDim / 4); i += blockDim.x) {
     const int key = i / (kHeadDim / 4), d4 = i % (kHeadDim / 4);
     f32x4 sk = {0.f, 0.f, 0.f, 0.f}, sv = {0.f, 0.f, 0.f, 0.f};
     for (int p = 0; p < r.nparts; ++p) {
@@ -411,7 +488,8 @@ int launch_bwd_bf16(const LaunchArgs& a) {
   if (qblocks == 0 || qblocks > 0x7fffffffu || kblocks > 0x7fffffffu) return DTA_ERR_UNSUPPORTED;
   if (a.stages & DTA_BWD_DELTA) {
     delta_bf16_kernel<<<(unsigned)((rows + 15) / 16), 256, 0, st>>>(
-        (const uint16_t*)a.o, (const uint16_t*)a.d_o, a.delta, rows);
+        (const uint16_t*)a.o, (const uint16_t*)a.d_o, a.lse_in, a.delta, a.lse2,
+        1.f / a.p.softmax_scale, rows);
     { int ls = launch_status(__func__); if (ls != DTA_OK) return ls; }
   }
   if (a.stages & DTA_BWD_DQ) {
@@ -424,11 +502,11 @@ int launch_bwd_bf16(const LaunchArgs& a) {
   if (a.stages & DTA_BWD_DKDV) {
     dkdv_bf16_kernel<<<(unsigned)kblocks, kKvThreads, 0, st>>>(
         a.sched->d_kv_items, a.d_kend, (const uint16_t*)a.q, (const uint16_t*)a.k,
-        (const uint16_t*)a.v, (const uint16_t*)a.d_o, a.lse_in, a.delta, (uint16_t*)a.dk,
+        (const uint16_t*)a.v, (const uint16_t*)a.d_o, a.lse2, a.delta, (uint16_t*)a.dk,
         (uint16_t*)a.dv, a.partial, a.p.n_q_heads, a.p.n_kv_heads, a.p.softmax_scale);
     { int ls = launch_status(__func__); if (ls != DTA_OK) return ls; }
     if (!a.sched->kv_reduce.empty()) {
-      dkdv_reduce_kernel<<<(unsigned)(a.sched->kv_reduce.size() * a.p.n_kv_heads), 256, 0, st>>>(
+      dkdv_reduce_kernel<<<(unsigned)(a.sched->kv_reduce.size() * a.p.n_kv_heads * 8), 256, 0, st>>>(
           a.sched->d_kv_reduce, a.partial, (uint16_t*)a.dk, (uint16_t*)a.dv, a.p.n_kv_heads,
           a.p.softmax_scale);
       { int ls = launch_status(__func__); if (ls != DTA_OK) return ls; }

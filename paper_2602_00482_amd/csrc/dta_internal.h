@@ -127,6 +127,7 @@ struct LaunchArgs {
   void *o_out, *dq, *dk, *dv;
   float* lse_out;
   float* delta;  // workspace: D[t,h] = dO.O
+  float* lse2;   // workspace (bf16 path): -lse / softmax_scale, written with delta (there: -D)
   float* partial;  // workspace: fp32 partial dK/dV of split key tiles
   uint32_t stages;  // backward stages to launch (DTA_BWD_*)
   void* stream;

@@ -172,7 +172,32 @@ __device__ __forceinline__ void tile_async_load(uint16_t* tile, const uint16_t* 
   }
 }
 
-__device__ __forceinline__ void async_wait_all() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// Starts the copy of 64 floats into dst[0..63] (LDS): lane l of the calling
+// wave fetches base[elem_off] with its own elem_off, so the copy can permute.
+// One wave calls this; completion as for tile_async_load.
+__device__ __forceinline__ void row_async_load(float* dst, const float* base, uint32_t elem_off) {
+  const uint32_t dst_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)dst;
+  const uint64_t base_bits = (uint64_t)(uintptr_t)base;
+  const uint32_t base_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(base_bits >> 32));
+  const uint32_t base_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)base_bits);
+  const uint64_t sbase = ((uint64_t)base_hi << 32) | (uint64_t)base_lo;
+  const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(dst_addr);
+  const uint32_t voff = elem_off * 4;
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dword %0, %1"
+               :
+               : "v"(voff), "s"(sbase), "s"(lds_addr)
+               : "memory");
+}
+
+// Waits for every vector-memory load of this wave, the tile copies included.
+// Issued through the builtin (vmcnt = 0, other counters untouched) so that the
+// compiler's own wait tracking sees it: otherwise it keeps loads from before a
+// loop pending across the back edge and adds partial vmcnt waits inside the
+// loop, which stall on the copies in flight.
+__device__ __forceinline__ void async_wait_all() {
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  asm volatile("" ::: "memory");
+}
 
 // Per-lane element offsets into a tile; add compile-time constants per read.
 // Row operand (lane = position c of a 32-block, half hh): 8 elements at

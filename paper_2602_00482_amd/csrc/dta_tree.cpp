@@ -289,7 +289,10 @@ Schedule& get_schedule(dta_tree* tree, int bm, int bn, int hkv, int group) {
 int validate_params(const dta_attn_params_t* p) {
   if (!p) return DTA_ERR_INVALID_ARG;
   if (p->n_q_heads < 1 || p->n_kv_heads < 1) return DTA_ERR_INVALID_ARG;
-  if (!(p->softmax_scale == p->softmax_scale)) return DTA_ERR_INVALID_ARG;  // NaN
+  // finite and nonzero (the bf16 backward divides by it)
+  if (!(p->softmax_scale == p->softmax_scale) || p->softmax_scale == 0.f ||
+      p->softmax_scale - p->softmax_scale != 0.f)
+    return DTA_ERR_INVALID_ARG;
   if (p->n_q_heads % p->n_kv_heads != 0) return DTA_ERR_UNSUPPORTED;
   if (p->dtype == DTA_F32) {
     if (p->head_dim != 64 && p->head_dim != 128) return DTA_ERR_UNSUPPORTED;
