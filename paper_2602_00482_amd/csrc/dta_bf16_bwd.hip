@@ -320,50 +320,68 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
     int tid_now = threadIdx.x;
     asm volatile("" : "+v"(tid_now));
     const float* stat = &sm.stat[buf][0][4 * ((tid_now >> 5) & 1)];
-    // a chunk none of this wave's keys can see contributes nothing (wave-uniform)
-    const bool wave_sees = r0 + nv > wave_lo && r0 < wave_hi;
-#pragma unroll
-    for (int mq = 0; mq < 2; ++mq) {
-      if (!wave_sees) continue;
-      // accumulators start from -lse/scale and -delta of their rows (values
-      // 4*e4 .. 4*e4+3 of a lane are four consecutive matrix positions)
+    // Half a chunk (32 query rows) against this wave's 32 keys, as one
+    // straight-line block in four phases.  Each phase pairs matrix products with
+    // the vector-ALU work of the previous phase's result, so that both pipes of
+    // the SIMD are busy from within one wave:
+    //   1  S  = -lse/scale + Q K^T
+    //   2  dP = -delta + dO V^T      |  P = exp(scale * S)
+    //      (mask P where the chunk needs it), pack P
+    //   3  dV += P^T dO              |  dS = P * dP, pack dS
+    //   4  dK += dS^T Q
+    // The accumulators start from the row statistics (values 4*e4 .. 4*e4+3 of a
+    // lane are four consecutive matrix positions), so no subtraction is left.
+    auto half = [&](auto mq_c) {
+      constexpr int mq = decltype(mq_c)::value;
+      // The issue order is written out by hand: operand reads run kAhead
+      // products ahead (which also bounds their registers), and a scheduling
+      // barrier after each product keeps the compiler from regrouping the
+      // vector-ALU work away from the product it is meant to run under.
+      constexpr int kAhead = 2;
+      auto k_op = [&](int ks) {
+        return ks < kRegK ? Kr[ks < kRegK ? ks : 0]
+                          : *reinterpret_cast<const bf16x8*>(stash + (ks - kRegK) * 512);
+      };
+      auto v_op = [&](int ks) {
+        return ks < kRegV ? Vr[ks < kRegV ? ks : 0]
+                          : *reinterpret_cast<const bf16x8*>(stash + (kStashK + ks - kRegV) * 512);
+      };
       f32x16 S, dP;
+      bf16x8 a[8];
+      // ---- phase 1
 #pragma unroll
       for (int e4 = 0; e4 < 4; ++e4) {
         const f32x4 ls = *reinterpret_cast<const f32x4*>(stat + (32 * mq + 8 * e4));
-        const f32x4 dl = *reinterpret_cast<const f32x4*>(stat + (kBQ + 32 * mq + 8 * e4));
 #pragma unroll
-        for (int j = 0; j < 4; ++j) { S[4 * e4 + j] = ls[j]; dP[4 * e4 + j] = dl[j]; }
+        for (int j = 0; j < 4; ++j) S[4 * e4 + j] = ls[j];
       }
+#pragma unroll
+      for (int ks = 0; ks < kAhead; ++ks) a[ks] = tile_row8(Qt, mq, ks);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 qa = tile_row8(Qt, mq, ks);
-        const bf16x8 da = tile_row8(dOt, mq, ks);
-        const bf16x8 kb = ks < kRegK ? Kr[ks < kRegK ? ks : 0]
-                                     : *reinterpret_cast<const bf16x8*>(stash + (ks - kRegK) * 512);
-        const bf16x8 vb = ks < kRegV ? Vr[ks < kRegV ? ks : 0]
-                                     : *reinterpret_cast<const bf16x8*>(stash + (kStashK + ks - kRegV) * 512);
-        S = mfma32(qa, kb, S);
-        dP = mfma32(da, vb, dP);
+        if (ks + kAhead < 8) a[ks + kAhead] = tile_row8(Qt, mq, ks + kAhead);
+        S = mfma32(a[ks], k_op(ks), S);
+        __builtin_amdgcn_sched_barrier(0);
       }
-      // Fixed software pipeline for this phase: operand reads run two k-steps
-      // ahead of the matrix products and no further, which bounds the registers
-      // the reads in flight can take (0x100 = LDS read, 0x008 = MFMA).
-      __builtin_amdgcn_sched_group_barrier(0x100, 8 + 4, 0);
+      // ---- phase 2
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      for (int e4 = 0; e4 < 4; ++e4) {
+        const f32x4 dl = *reinterpret_cast<const f32x4*>(stat + (kBQ + 32 * mq + 8 * e4));
+#pragma unroll
+        for (int j = 0; j < 4; ++j) dP[4 * e4 + j] = dl[j];
       }
-      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 2 + (kStashK > 1) + (kStashV > 1), 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 2 + (kStashK > 0) + (kStashV > 0), 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-      __builtin_amdgcn_sched_barrier(0);   // the next phase's LDS reads stay behind this point
 #pragma unroll
-      for (int e = 0; e < 16; ++e) S[e] = __builtin_amdgcn_exp2f(S[e] * sc);
+      for (int ks = 0; ks < kAhead; ++ks) a[ks] = tile_row8(dOt, mq, ks);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        if (ks + kAhead < 8) a[ks + kAhead] = tile_row8(dOt, mq, ks + kAhead);
+        dP = mfma32(a[ks], v_op(ks), dP);
+        S[2 * ks] = __builtin_amdgcn_exp2f(S[2 * ks] * sc);
+        S[2 * ks + 1] = __builtin_amdgcn_exp2f(S[2 * ks + 1] * sc);
+        __builtin_amdgcn_sched_barrier(0);
+      }
       if (need_mask) {   // query row t sees this lane's key iff kcol <= t < kend[kcol]
         // row_of_acc(mq, e, hh) = 4*hh + (compile-time part): compare against per-lane bounds
         const int2 bnd = sm.bound[tid_now];
@@ -375,35 +393,38 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
           S[e] = ((rc >= lo) & (rc < hi)) ? S[e] : 0.f;
         }
       }
+      // ---- phase 3: product i uses columns 32*(i/2).., rows 16*(i%2).. of dO
+      const bf16x8 Pb[2] = {pack8(S, 0), pack8(S, 1)};
+      bf16x8 dSb[2];
 #pragma unroll
-      for (int e = 0; e < 16; ++e) dP[e] *= S[e];
-      const bf16x8 Pb0 = pack8(S, 0), Pb1 = pack8(S, 1);
-      const bf16x8 dSb0 = pack8(dP, 0), dSb1 = pack8(dP, 1);
+      for (int i = 0; i < kAhead; ++i) a[i] = tile_col8(dOc, 32 * mq + 16 * (i & 1), 32 * (i >> 1));
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int dmb = 0; dmb < 4; ++dmb) {
-        const bf16x8 dot0 = tile_col8(dOc, 32 * mq, 32 * dmb);
-        const bf16x8 dot1 = tile_col8(dOc, 32 * mq + 16, 32 * dmb);
-        dV[dmb] = mfma32(dot0, Pb0, dV[dmb]);
-        dV[dmb] = mfma32(dot1, Pb1, dV[dmb]);
+      for (int i = 0; i < 8; ++i) {
+        if (i + kAhead < 8)
+          a[i + kAhead] = tile_col8(dOc, 32 * mq + 16 * ((i + kAhead) & 1), 32 * ((i + kAhead) >> 1));
+        dV[i >> 1] = mfma32(a[i], Pb[i & 1], dV[i >> 1]);
+        dSb[i >> 2][2 * (i & 3)] = (__bf16)(dP[2 * i] * S[2 * i]);
+        dSb[i >> 2][2 * (i & 3) + 1] = (__bf16)(dP[2 * i + 1] * S[2 * i + 1]);
+        __builtin_amdgcn_sched_barrier(0);
       }
+      // ---- phase 4
 #pragma unroll
-      for (int dmb = 0; dmb < 4; ++dmb) {
-        const bf16x8 qt0 = tile_col8(Qc, 32 * mq, 32 * dmb);
-        const bf16x8 qt1 = tile_col8(Qc, 32 * mq + 16, 32 * dmb);
-        dK[dmb] = mfma32(qt0, dSb0, dK[dmb]);
-        dK[dmb] = mfma32(qt1, dSb1, dK[dmb]);
-      }
-      // same idea: the transposing reads run kTrAhead matrix products ahead
-      constexpr int kTrAhead = 3;
-      __builtin_amdgcn_sched_group_barrier(0x100, 2 * kTrAhead, 0);
-#pragma unroll
-      for (int i = 0; i < 16 - kTrAhead; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-      }
-      __builtin_amdgcn_sched_group_barrier(0x008, kTrAhead, 0);
+      for (int i = 0; i < kAhead; ++i) a[i] = tile_col8(Qc, 32 * mq + 16 * (i & 1), 32 * (i >> 1));
       __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        if (i + kAhead < 8)
+          a[i + kAhead] = tile_col8(Qc, 32 * mq + 16 * ((i + kAhead) & 1), 32 * ((i + kAhead) >> 1));
+        dK[i >> 1] = mfma32(a[i], dSb[i & 1], dK[i >> 1]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+    // a chunk none of this wave's keys can see contributes nothing (wave-uniform)
+    const bool wave_sees = r0 + nv > wave_lo && r0 < wave_hi;
+    if (wave_sees) {
+      half(std::integral_constant<int, 0>{});
+      half(std::integral_constant<int, 1>{});
     }
   };
   for (int it = tile.it_begin; it < total; it += 2) {
