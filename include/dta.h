@@ -18,7 +18,9 @@
  *  - attention calls only enqueue work on the given HIP stream and do not
  *    synchronise it.  The first attention call on a tree (or an explicit
  *    dta_tree_attn_prepare) allocates and uploads the tree's device metadata
- *    with a blocking copy; later calls allocate nothing;
+ *    (stream-ordered allocation and copy on a stream the library owns; the call
+ *    waits for that copy only, never for the caller's streams); later calls
+ *    allocate nothing;
  *  - tensors are dense row-major [T, H, head_dim] with T = unique tree tokens in
  *    the packed DFS order defined by dta_tree_build.
  */
@@ -121,7 +123,10 @@ int dta_tree_layout(const dta_tree_t* tree, dta_tree_layout_t* out);
 int dta_tree_schedule_info(dta_tree_t* tree, const dta_attn_params_t* params,
                            dta_schedule_info_t* out);
 
-/* Frees host and device memory of the tree.  NULL is allowed. */
+/* Frees host and device memory of the tree.  NULL is allowed.  Does not block:
+ * the device copies are released once the attention calls already enqueued
+ * for this tree have finished, so a tree may be destroyed right after its last
+ * launch. */
 void dta_tree_destroy(dta_tree_t* tree);
 
 /* Bytes of device workspace dta_tree_attn_fwd (is_bwd = 0) or dta_tree_attn_bwd
@@ -131,7 +136,8 @@ size_t dta_tree_attn_workspace_bytes(const dta_tree_t* tree, const dta_attn_para
                                      int is_bwd);
 
 /* Optional: allocate and upload the tree's device metadata for this head
- * configuration now (blocking), so that later attention calls only enqueue. */
+ * configuration now (waits for the upload only), so that later attention calls
+ * only enqueue. */
 int dta_tree_attn_prepare(dta_tree_t* tree, const dta_attn_params_t* params);
 
 /*

@@ -3,6 +3,10 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
+#include <cstring>
+#include <initializer_list>
+#include <mutex>
+#include <vector>
 #include <new>
 
 #include "dta_internal.h"
@@ -32,32 +36,99 @@ size_t bwd_workspace_bytes(dta_tree* tree, const dta::TileChoice& tc, const dta_
   return bytes;
 }
 
-template <typename T>
-int upload(const std::vector<T>& host, T** dev) {
-  if (*dev) {
-    (void)hipFree(*dev);
-    *dev = nullptr;
+// Device metadata lives in stream-ordered allocations made and filled on a
+// stream of the library's own (non-blocking, default priority, one per device,
+// kept until the process ends), so that preparing the next tree neither waits
+// for kernels the caller still has in flight nor, on release, for the device
+// to go idle.
+// Releases go to a second such stream: they wait there for the caller's
+// kernels, and an upload queued behind that wait would wait as well.
+constexpr int kMaxDevices = 64;
+enum { kUpload = 0, kRelease = 1 };
+std::mutex g_stream_mu;
+hipStream_t g_stream[kMaxDevices][2];
+bool g_stream_ok[kMaxDevices];
+
+int internal_stream(int dev, int which, hipStream_t* out) {
+  if (dev < 0 || dev >= kMaxDevices) return DTA_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_stream_mu);
+  if (!g_stream_ok[dev]) {
+    for (int i = 0; i < 2; ++i)
+      if (hipStreamCreateWithFlags(&g_stream[dev][i], hipStreamNonBlocking) != hipSuccess) {
+        fprintf(stderr, "dta: cannot create the metadata streams\n");
+        (void)hipGetLastError();
+        if (i == 1) (void)hipStreamDestroy(g_stream[dev][0]);
+        return DTA_ERR_HIP;
+      }
+    g_stream_ok[dev] = true;
   }
-  size_t bytes = host.size() * sizeof(T);
-  if (bytes == 0) bytes = sizeof(T);
-  if (hipMalloc((void**)dev, bytes) != hipSuccess) {
-    *dev = nullptr;
+  *out = g_stream[dev][which];
+  return DTA_OK;
+}
+
+struct Part {
+  const void* src;
+  size_t bytes;
+  void** dst;
+};
+
+// One allocation holding every part (each 256-byte aligned), filled from the
+// host and complete on return.
+int upload_parts(hipStream_t st, std::initializer_list<Part> parts, void** blob) {
+  size_t total = 0;
+  for (const Part& p : parts) total += round_up(p.bytes ? p.bytes : 1, 256);
+  std::vector<char> staging;
+  try {
+    staging.resize(total);
+  } catch (const std::bad_alloc&) {
+    return DTA_ERR_ALLOC;
+  }
+  if (hipMallocAsync(blob, total, st) != hipSuccess) {
+    *blob = nullptr;
     (void)hipGetLastError();
     return DTA_ERR_ALLOC;
   }
-  if (!host.empty()) {
-    hipError_t e = hipMemcpy(*dev, host.data(), host.size() * sizeof(T), hipMemcpyHostToDevice);
-    if (e != hipSuccess) {
-      fprintf(stderr, "dta: metadata upload: %s\n", hipGetErrorString(e));
-      (void)hipGetLastError();
-      return DTA_ERR_HIP;
-    }
+  size_t off = 0;
+  for (const Part& p : parts) {
+    if (p.bytes) memcpy(staging.data() + off, p.src, p.bytes);
+    *p.dst = (char*)*blob + off;
+    off += round_up(p.bytes ? p.bytes : 1, 256);
+  }
+  hipError_t e = hipMemcpyAsync(*blob, staging.data(), total, hipMemcpyHostToDevice, st);
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
+  if (e != hipSuccess) {
+    fprintf(stderr, "dta: metadata upload: %s\n", hipGetErrorString(e));
+    (void)hipGetLastError();
+    (void)hipFreeAsync(*blob, st);
+    *blob = nullptr;
+    return DTA_ERR_HIP;
   }
   return DTA_OK;
 }
 
+// Releases a blob once the launches recorded in the tree's last_use event are
+// done, without blocking the host.
+void release_blob(dta_tree* tree, void* blob, int dev) {
+  if (!blob) return;
+  int cur = -1;
+  hipStream_t st;
+  if (hipGetDevice(&cur) == hipSuccess && cur == dev &&
+      internal_stream(dev, kRelease, &st) == DTA_OK) {
+    if (tree->used) (void)hipStreamWaitEvent(st, (hipEvent_t)tree->last_use, 0);
+    if (hipFreeAsync(blob, st) == hipSuccess) return;
+  }
+  (void)hipGetLastError();
+  (void)hipFree(blob);   // other device current, or no stream: blocking release
+}
+
+template <typename T>
+Part part_of(const std::vector<T>& v, T** dst) {
+  return Part{v.data(), v.size() * sizeof(T), (void**)dst};
+}
+
 // Makes sure the schedule for (bm, bn) and kend[] are resident on the current
-// device.  Takes the tree lock; blocking on first use, a no-op afterwards.
+// device.  Takes the tree lock; blocking (on the upload only) on first use, a
+// no-op afterwards.
 int ensure_device(dta_tree* tree, const dta::TileChoice& tc, const dta_attn_params_t* p,
                   dta::Schedule** out) {
   std::lock_guard<std::mutex> lock(tree->mu);
@@ -74,19 +145,55 @@ int ensure_device(dta_tree* tree, const dta::TileChoice& tc, const dta_attn_para
     return DTA_ERR_ALLOC;
   }
   int st;
+  if (tree->kend_device == dev && s->device == dev) {
+    *out = s;
+    return DTA_OK;
+  }
+  hipStream_t us;
+  if ((st = internal_stream(dev, kUpload, &us)) != DTA_OK) return st;
+  if (!tree->last_use) {
+    hipEvent_t ev;
+    if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) {
+      (void)hipGetLastError();
+      return DTA_ERR_HIP;
+    }
+    tree->last_use = ev;
+  }
   if (tree->kend_device != dev) {
-    if ((st = upload(tree->token_kend, &tree->d_token_kend)) != DTA_OK) return st;
+    release_blob(tree, tree->d_token_kend, tree->kend_device);
+    tree->d_token_kend = nullptr;
+    tree->kend_device = -1;
+    void* blob = nullptr;
+    if ((st = upload_parts(us, {part_of(tree->token_kend, &tree->d_token_kend)}, &blob)) != DTA_OK)
+      return st;
     tree->kend_device = dev;
   }
   if (s->device != dev) {
-    if ((st = upload(s->q_tiles, &s->d_q_tiles)) != DTA_OK) return st;
-    if ((st = upload(s->segs, &s->d_segs)) != DTA_OK) return st;
-    if ((st = upload(s->kv_tiles, &s->d_kv_tiles)) != DTA_OK) return st;
-    if ((st = upload(s->kv_items, &s->d_kv_items)) != DTA_OK) return st;
-    if ((st = upload(s->kv_reduce, &s->d_kv_reduce)) != DTA_OK) return st;
+    release_blob(tree, s->d_blob, s->device);
+    s->d_blob = nullptr;
+    s->device = -1;
+    if ((st = upload_parts(us,
+                           {part_of(s->q_tiles, &s->d_q_tiles), part_of(s->segs, &s->d_segs),
+                            part_of(s->kv_tiles, &s->d_kv_tiles),
+                            part_of(s->kv_items, &s->d_kv_items),
+                            part_of(s->kv_reduce, &s->d_kv_reduce)},
+                           &s->d_blob)) != DTA_OK)
+      return st;
     s->device = dev;
   }
   *out = s;
+  return DTA_OK;
+}
+
+// After a launch on `stream` that reads the tree's device copies.
+int mark_use(dta_tree* tree, void* stream, int launch_result) {
+  if (launch_result != DTA_OK) return launch_result;
+  std::lock_guard<std::mutex> lock(tree->mu);
+  if (hipEventRecord((hipEvent_t)tree->last_use, (hipStream_t)stream) != hipSuccess) {
+    (void)hipGetLastError();
+    return DTA_ERR_HIP;
+  }
+  tree->used = true;
   return DTA_OK;
 }
 
@@ -111,15 +218,9 @@ extern "C" {
 
 void dta_tree_destroy(dta_tree_t* tree) {
   if (!tree) return;
-  if (tree->d_token_kend) (void)hipFree(tree->d_token_kend);
-  for (auto& kv : tree->schedules) {
-    dta::Schedule& s = kv.second;
-    if (s.d_q_tiles) (void)hipFree(s.d_q_tiles);
-    if (s.d_segs) (void)hipFree(s.d_segs);
-    if (s.d_kv_tiles) (void)hipFree(s.d_kv_tiles);
-    if (s.d_kv_items) (void)hipFree(s.d_kv_items);
-    if (s.d_kv_reduce) (void)hipFree(s.d_kv_reduce);
-  }
+  release_blob(tree, tree->d_token_kend, tree->kend_device);
+  for (auto& kv : tree->schedules) release_blob(tree, kv.second.d_blob, kv.second.device);
+  if (tree->last_use) (void)hipEventDestroy((hipEvent_t)tree->last_use);
   delete tree;
 }
 
@@ -166,7 +267,8 @@ int dta_tree_attn_fwd(dta_tree_t* tree, const dta_attn_params_t* params, const v
   a.o_out = o;
   a.lse_out = lse;
   a.stream = hip_stream;
-  return params->dtype == DTA_F32 ? dta::launch_fwd_f32(a) : dta::launch_fwd_bf16(a);
+  return mark_use(tree, hip_stream,
+                  params->dtype == DTA_F32 ? dta::launch_fwd_f32(a) : dta::launch_fwd_bf16(a));
 }
 
 int dta_tree_attn_bwd_stages(dta_tree_t* tree, const dta_attn_params_t* params, const void* q,
@@ -209,7 +311,8 @@ int dta_tree_attn_bwd_stages(dta_tree_t* tree, const dta_attn_params_t* params, 
   a.partial = (float*)((char*)workspace + 2 * delta_bytes(tree, params));
   a.stages = stage_mask;
   a.stream = hip_stream;
-  return params->dtype == DTA_F32 ? dta::launch_bwd_f32(a) : dta::launch_bwd_bf16(a);
+  return mark_use(tree, hip_stream,
+                  params->dtype == DTA_F32 ? dta::launch_bwd_f32(a) : dta::launch_bwd_bf16(a));
 }
 
 int dta_tree_attn_bwd(dta_tree_t* tree, const dta_attn_params_t* params, const void* q,

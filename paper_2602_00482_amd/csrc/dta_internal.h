@@ -72,8 +72,10 @@ struct Schedule {
   std::vector<KvReduce> kv_reduce;
   int64_t n_slots = 0;
   int64_t fwd_tile_pairs = 0, bwd_tile_pairs = 0;
-  // device copies (owned; freed with the tree)
+  // device copies: one allocation (d_blob, owned, released with the tree) that
+  // the typed pointers below point into
   int device = -1;
+  void* d_blob = nullptr;
   QTile* d_q_tiles = nullptr;
   KeySeg* d_segs = nullptr;
   KvTile* d_kv_tiles = nullptr;
@@ -96,6 +98,8 @@ struct dta_tree {
   std::map<uint64_t, dta::Schedule> schedules;
   int32_t* d_token_kend = nullptr;
   int kend_device = -1;
+  void* last_use = nullptr;   // hipEvent_t recorded after every launch that reads the device copies
+  bool used = false;          // last_use has been recorded at least once
   std::mutex mu;
 };
 

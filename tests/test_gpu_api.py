@@ -106,3 +106,25 @@ def test_runtime_argument_errors():
     assert lib.dta_tree_attn_bwd(*base, ptr(ws), need, z) == 0
     torch.cuda.synchronize()
     tree.destroy()
+
+
+def test_destroy_right_after_launch_and_metadata_reuse():
+    """A tree may be destroyed while its kernels are still queued; trees built
+    back to back (whose metadata allocations get recycled) must not disturb
+    each other's results."""
+    outs = []
+    for rep in range(2):
+        res = []
+        for seed in (11, 12, 13, 14):
+            rng = np.random.default_rng(seed)
+            parent, seg = random_tree(rng, 9 + seed % 3, 700 + 50 * (seed % 4))
+            x, t, tree, p, _ = _setup(parent, seg, 8, 2, 128, "bf16", seed=seed)
+            o, lse = dta.tree_attn_fwd(tree, p, t["q"], t["k"], t["v"])
+            grads = dta.tree_attn_bwd(tree, p, t["q"], t["k"], t["v"], o, lse, t["do"])
+            tree.destroy()            # kernels may still be running
+            res.append((o, lse) + tuple(grads))
+        torch.cuda.synchronize()
+        outs.append([[a.float().cpu() for a in r] for r in res])
+    for a, b in zip(outs[0], outs[1]):
+        for u, v in zip(a, b):
+            assert torch.equal(u, v)

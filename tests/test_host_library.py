@@ -136,7 +136,10 @@ def test_error_codes():
                       (dta.AttnParams(4, 2, 96, 1.0, dta.F32), -3),        # head_dim
                       (dta.AttnParams(4, 2, 64, 1.0, dta.BF16), -3),       # bf16 needs 128
                       (dta.AttnParams(4, 2, 128, 1.0, 7), -3),             # dtype
-                      (dta.AttnParams(0, 1, 128, 1.0, dta.BF16), -1)):
+                      (dta.AttnParams(0, 1, 128, 1.0, dta.BF16), -1),
+                      (dta.AttnParams(4, 2, 128, 0.0, dta.BF16), -1),      # scale: finite, nonzero
+                      (dta.AttnParams(4, 2, 128, float("inf"), dta.BF16), -1),
+                      (dta.AttnParams(4, 2, 64, float("nan"), dta.F32), -1)):
         with pytest.raises(dta.DtaError) as err:
             tree.schedule_info(bad)
         assert err.value.status == want
