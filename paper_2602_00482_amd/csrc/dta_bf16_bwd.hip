@@ -101,7 +101,9 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
       dOr[ks] = *reinterpret_cast<const bf16x8*>(dop + 16 * ks);
     }
   }
-  const float lse2 = lse[rh] * kLog2e, ndlt = neg_delta[rh];
+  // accumulator start values of this lane's query row: the scores start from
+  // -lse/scale so that P = exp(scale * acc), dP from -delta so that dS = P * acc
+  const float nlse = -lse[rh] / scale, ndlt = neg_delta[rh];
 
   f32x16 dQ[4];
 #pragma unroll
@@ -144,20 +146,37 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
     const uint16_t* Vt = Vs[buf] + rlo;
     const uint16_t* Kc = Ks[buf] + clo;
 
+    // Per 32-key half, in an issue order written out by hand (a scheduling
+    // barrier after every product keeps it): operand reads run kAhead products
+    // ahead, and the exponentials of S are issued under the products of dP so
+    // that both pipes of the SIMD work from within one wave.
+    constexpr int kAhead = 2;
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb) {
       f32x16 S, dP;
+      bf16x8 a[8];
 #pragma unroll
-      for (int e = 0; e < 16; ++e) { S[e] = 0.f; dP[e] = 0.f; }
+      for (int e = 0; e < 16; ++e) { S[e] = nlse; dP[e] = ndlt; }   // start values: -lse/scale, -delta
+#pragma unroll
+      for (int ks = 0; ks < kAhead; ++ks) a[ks] = tile_row8(Kt, mb, ks);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 ka = tile_row8(Kt, mb, ks);
-        const bf16x8 va = tile_row8(Vt, mb, ks);
-        S = mfma32(ka, Qr[ks], S);
-        dP = mfma32(va, dOr[ks], dP);
+        if (ks + kAhead < 8) a[ks + kAhead] = tile_row8(Kt, mb, ks + kAhead);
+        S = mfma32(a[ks], Qr[ks], S);
+        __builtin_amdgcn_sched_barrier(0);
       }
 #pragma unroll
-      for (int e = 0; e < 16; ++e) S[e] = __builtin_amdgcn_exp2f(fmaf(S[e], sc, -lse2));
+      for (int ks = 0; ks < kAhead; ++ks) a[ks] = tile_row8(Vt, mb, ks);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        if (ks + kAhead < 8) a[ks + kAhead] = tile_row8(Vt, mb, ks + kAhead);
+        dP = mfma32(a[ks], dOr[ks], dP);
+        S[2 * ks] = __builtin_amdgcn_exp2f(S[2 * ks] * sc);
+        S[2 * ks + 1] = __builtin_amdgcn_exp2f(S[2 * ks + 1] * sc);
+        __builtin_amdgcn_sched_barrier(0);
+      }
       if (need_mask) {
 #pragma unroll
         for (int e4 = 0; e4 < 4; ++e4) {
@@ -171,16 +190,20 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
           }
         }
       }
+      // dQ^T += K^T dS^T over this 32-key half; product i uses columns
+      // 32*(i/2).., keys 16*(i%2).. of K
+      bf16x8 dSb[2];
 #pragma unroll
-      for (int e = 0; e < 16; ++e) S[e] *= dP[e] + ndlt;
-      const bf16x8 dSb0 = pack8(S, 0), dSb1 = pack8(S, 1);
-      // dQ^T += K^T dS^T over this 32-key half
+      for (int i = 0; i < kAhead; ++i) a[i] = tile_col8(Kc, 32 * mb + 16 * (i & 1), 32 * (i >> 1));
 #pragma unroll
-      for (int dmb = 0; dmb < 4; ++dmb) {
-        const bf16x8 kt0 = tile_col8(Kc, 32 * mb, 32 * dmb);
-        const bf16x8 kt1 = tile_col8(Kc, 32 * mb + 16, 32 * dmb);
-        dQ[dmb] = mfma32(kt0, dSb0, dQ[dmb]);
-        dQ[dmb] = mfma32(kt1, dSb1, dQ[dmb]);
+      for (int e = 0; e < 16; ++e) dSb[e >> 3][e & 7] = (__bf16)(S[e] * dP[e]);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        if (i + kAhead < 8)
+          a[i + kAhead] = tile_col8(Kc, 32 * mb + 16 * ((i + kAhead) & 1), 32 * ((i + kAhead) >> 1));
+        dQ[i >> 1] = mfma32(a[i], dSb[i & 1], dQ[i >> 1]);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
     buf ^= 1;
