@@ -78,6 +78,12 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
   __shared__ __attribute__((aligned(1024))) uint16_t Ks[2][kTileElems];
   __shared__ __attribute__((aligned(1024))) uint16_t Vs[2][kTileElems];
   __shared__ __attribute__((aligned(16))) int32_t kendS[2][kKeyChunk];
+  // The last k-step of this wave's Q and dO operands lives in LDS instead of
+  // registers (each lane reads back what it wrote): with all 16 in registers the
+  // kernel needs a few more than 256, and reloads from scratch memory would wait
+  // for, i.e. serialise, the tile copies in flight.
+  constexpr int kReg = 6;
+  __shared__ __attribute__((aligned(16))) uint16_t stashS[kDqThreads / 64][2 * (8 - kReg)][64 * 8];
 
   const int inner = blockIdx.x % (Hkv * hblocks);
   const QTile tile = tiles[blockIdx.x / (Hkv * hblocks)];
@@ -91,16 +97,32 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
 
   const int qrow = min(row_base + c, tile.t1 - 1);
   const size_t rh = (size_t)qrow * Hq + h;
-  bf16x8 Qr[8], dOr[8];
+  bf16x8 Qr[kReg], dOr[kReg];
+  uint16_t* stash = &stashS[w][0][l * 8];
   {
     const uint16_t* qp = q + rh * kHeadDim + 8 * hh;
     const uint16_t* dop = d_o + rh * kHeadDim + 8 * hh;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-      Qr[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
-      dOr[ks] = *reinterpret_cast<const bf16x8*>(dop + 16 * ks);
+      const bf16x8 qx = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
+      const bf16x8 dx = *reinterpret_cast<const bf16x8*>(dop + 16 * ks);
+      if (ks < kReg) {
+        Qr[ks < kReg ? ks : 0] = qx;
+        dOr[ks < kReg ? ks : 0] = dx;
+      } else {
+        *reinterpret_cast<bf16x8*>(stash + (2 * (ks - kReg)) * 512) = qx;
+        *reinterpret_cast<bf16x8*>(stash + (2 * (ks - kReg) + 1) * 512) = dx;
+      }
     }
   }
+  auto q_op = [&](int ks) {
+    return ks < kReg ? Qr[ks < kReg ? ks : 0]
+                     : *reinterpret_cast<const bf16x8*>(stash + (2 * (ks - kReg)) * 512);
+  };
+  auto do_op = [&](int ks) {
+    return ks < kReg ? dOr[ks < kReg ? ks : 0]
+                     : *reinterpret_cast<const bf16x8*>(stash + (2 * (ks - kReg) + 1) * 512);
+  };
   // accumulator start values of this lane's query row: the scores start from
   // -lse/scale so that P = exp(scale * acc), dP from -delta so that dS = P * acc
   const float nlse = -lse[rh] / scale, ndlt = neg_delta[rh];
@@ -146,66 +168,84 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
     const uint16_t* Vt = Vs[buf] + rlo;
     const uint16_t* Kc = Ks[buf] + clo;
 
-    // Per 32-key half, in an issue order written out by hand (a scheduling
-    // barrier after every product keeps it): operand reads run kAhead products
-    // ahead, and the exponentials of S are issued under the products of dP so
-    // that both pipes of the SIMD work from within one wave.
-    constexpr int kAhead = 2;
+    // The chunk's two 32-key halves as one sequence of 48 matrix products in
+    // six phases, in an issue order written out by hand (a scheduling barrier
+    // after every product keeps it):
+    //   S0 | dP0 + exp(S0) | S1 + dS0 | dP1 + exp(S1) | dQ0 + dS1 | dQ1
+    // The LDS operand of product i + kAhead is read before product i is issued,
+    // across phase boundaries too (ring of kAhead + 1 operands), and the
+    // vector-ALU work of a phase is issued under products that do not depend on
+    // it, so that both pipes of the SIMD work from within one wave.
+    constexpr int kAhead = 2, kRing = kAhead + 1;
+    f32x16 S[2], dP[2];
+    bf16x8 dSb[2][2];
+    bf16x8 a[kRing];
+    // LDS operand j of phase ph: K rows (S), V rows (dP), K columns (dQ^T += K^T
+    // dS^T: product j of a half uses columns 32*(j/2).., keys 16*(j%2).. of K)
+    auto fetch = [&](auto ph_c, int j) {
+      constexpr int ph = decltype(ph_c)::value;
+      if constexpr (ph == 0 || ph == 2) return tile_row8(Kt, ph >> 1, j);
+      else if constexpr (ph == 1 || ph == 3) return tile_row8(Vt, ph >> 1, j);
+      else return tile_col8(Kc, 32 * (ph - 4) + 16 * (j & 1), 32 * (j >> 1));
+    };
+    auto phase = [&](auto ph_c) {
+      constexpr int ph = decltype(ph_c)::value;
+      constexpr int mb = (ph >> 1) & 1;
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb) {
-      f32x16 S, dP;
-      bf16x8 a[8];
+      for (int j = 0; j < 8; ++j) {
+        const int i = 8 * ph + j;   // product number in the chunk
+        if (j + kAhead < 8) a[(i + kAhead) % kRing] = fetch(ph_c, j + kAhead);
+        else if (ph < 5) a[(i + kAhead) % kRing] = fetch(std::integral_constant<int, (ph < 5 ? ph + 1 : 5)>{}, j + kAhead - 8);
+        const bf16x8 av = a[i % kRing];
+        if constexpr (ph == 0 || ph == 2) {          // S(mb), starting from -lse/scale
+          if (j == 0) {
 #pragma unroll
-      for (int e = 0; e < 16; ++e) { S[e] = nlse; dP[e] = ndlt; }   // start values: -lse/scale, -delta
+            for (int e = 0; e < 16; ++e) S[mb][e] = nlse;
+          }
+          S[mb] = mfma32(av, q_op(j), S[mb]);
+        } else if constexpr (ph == 1 || ph == 3) {   // dP(mb), starting from -delta; P = exp(scale * S) under it
+          if (j == 0) {
 #pragma unroll
-      for (int ks = 0; ks < kAhead; ++ks) a[ks] = tile_row8(Kt, mb, ks);
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        if (ks + kAhead < 8) a[ks + kAhead] = tile_row8(Kt, mb, ks + kAhead);
-        S = mfma32(a[ks], Qr[ks], S);
+            for (int e = 0; e < 16; ++e) dP[mb][e] = ndlt;
+          }
+          dP[mb] = mfma32(av, do_op(j), dP[mb]);
+          S[mb][2 * j] = __builtin_amdgcn_exp2f(S[mb][2 * j] * sc);
+          S[mb][2 * j + 1] = __builtin_amdgcn_exp2f(S[mb][2 * j + 1] * sc);
+        } else {                                     // dQ
+          dQ[j >> 1] = mfma32(av, dSb[ph - 4][j & 1], dQ[j >> 1]);
+        }
+        if constexpr (ph == 2 || ph == 4) {          // dS of the previous half = P * dP, two values per product
+          constexpr int pv = (ph - 2) >> 1;
+          dSb[pv][j >> 2][2 * (j & 3)] = (__bf16)(S[pv][2 * j] * dP[pv][2 * j]);
+          dSb[pv][j >> 2][2 * (j & 3) + 1] = (__bf16)(S[pv][2 * j + 1] * dP[pv][2 * j + 1]);
+        }
         __builtin_amdgcn_sched_barrier(0);
       }
+      if constexpr (ph == 1 || ph == 3) {
+        if (need_mask) {   // uniform branch
 #pragma unroll
-      for (int ks = 0; ks < kAhead; ++ks) a[ks] = tile_row8(Vt, mb, ks);
-      __builtin_amdgcn_sched_barrier(0);
+          for (int e4 = 0; e4 < 4; ++e4) {
+            const int4 ke = *reinterpret_cast<const int4*>(&kendS[buf][32 * mb + 8 * e4 + 4 * hh]);
+            const int kev[4] = {ke.x, ke.y, ke.z, ke.w};
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        if (ks + kAhead < 8) a[ks + kAhead] = tile_row8(Vt, mb, ks + kAhead);
-        dP = mfma32(a[ks], dOr[ks], dP);
-        S[2 * ks] = __builtin_amdgcn_exp2f(S[2 * ks] * sc);
-        S[2 * ks + 1] = __builtin_amdgcn_exp2f(S[2 * ks + 1] * sc);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      if (need_mask) {
-#pragma unroll
-        for (int e4 = 0; e4 < 4; ++e4) {
-          const int4 ke = *reinterpret_cast<const int4*>(&kendS[buf][32 * mb + 8 * e4 + 4 * hh]);
-          const int kev[4] = {ke.x, ke.y, ke.z, ke.w};
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const int e = 4 * e4 + j;
-            const bool ok = (cc0 + row_of_acc(mb, e, hh) <= qrow) & (qrow < kev[j]);
-            S[e] = ok ? S[e] : 0.f;
+            for (int jj = 0; jj < 4; ++jj) {
+              const int e = 4 * e4 + jj;
+              const bool ok = (cc0 + row_of_acc(mb, e, hh) <= qrow) & (qrow < kev[jj]);
+              S[mb][e] = ok ? S[mb][e] : 0.f;
+            }
           }
         }
       }
-      // dQ^T += K^T dS^T over this 32-key half; product i uses columns
-      // 32*(i/2).., keys 16*(i%2).. of K
-      bf16x8 dSb[2];
+    };
 #pragma unroll
-      for (int i = 0; i < kAhead; ++i) a[i] = tile_col8(Kc, 32 * mb + 16 * (i & 1), 32 * (i >> 1));
-#pragma unroll
-      for (int e = 0; e < 16; ++e) dSb[e >> 3][e & 7] = (__bf16)(S[e] * dP[e]);
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        if (i + kAhead < 8)
-          a[i + kAhead] = tile_col8(Kc, 32 * mb + 16 * ((i + kAhead) & 1), 32 * ((i + kAhead) >> 1));
-        dQ[i >> 1] = mfma32(a[i], dSb[i & 1], dQ[i >> 1]);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    }
+    for (int j = 0; j < kAhead; ++j) a[j] = fetch(std::integral_constant<int, 0>{}, j);
+    __builtin_amdgcn_sched_barrier(0);
+    phase(std::integral_constant<int, 0>{});
+    phase(std::integral_constant<int, 1>{});
+    phase(std::integral_constant<int, 2>{});
+    phase(std::integral_constant<int, 3>{});
+    phase(std::integral_constant<int, 4>{});
+    phase(std::integral_constant<int, 5>{});
     buf ^= 1;
   }
 
