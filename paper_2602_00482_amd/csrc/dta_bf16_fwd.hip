@@ -24,6 +24,16 @@ namespace {
 
 constexpr int kThreads = 512;
 
+// max over both halves of the wave: lane l gets max(x[l], x[l ^ 32]).  The
+// lane-half swap (v_permlane32_swap: upper 32 lanes of the first operand <->
+// lower 32 lanes of the second) runs in the vector ALU, without the LDS round
+// trip of a shuffle.
+__device__ __forceinline__ float max_across_halves(float x) {
+  const unsigned u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
 __global__ __launch_bounds__(kThreads) void fwd_bf16_kernel(
     const QTile* __restrict__ tiles, const KeySeg* __restrict__ segs,
     const int32_t* __restrict__ kend, const uint16_t* __restrict__ q,
@@ -140,7 +150,7 @@ __global__ __launch_bounds__(kThreads) void fwd_bf16_kernel(
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
       for (int e = 0; e < 16; ++e) mx = fmaxf(mx, S[mb][e]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    mx = max_across_halves(mx);
     const float mnew = fmaxf(m, mx);
     const float mref = mnew == -INFINITY ? 0.f : mnew;
     const float alpha = __builtin_amdgcn_exp2f((m - mref) * sc);
