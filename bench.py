@@ -38,10 +38,13 @@ PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 # flop per unique pair per q head, in units of head_dim, that each launch must do
 KERNEL_FLOP_D = {"fwd": 4, "dq": 6, "dkdv": 8}
 # HBM bytes per launch (read + written) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
-# this workload, each counter scaled by what it reads for a plain 1 GiB copy (FETCH_SIZE x2.000,
-# WRITE_SIZE x1.000); see profiles/cfg2_grpo_tree_hbm_traffic.md.  Not measured live.
+# these workloads (`bench.py --traffic-probe --config N`), each counter scaled by what it reads
+# for the plain 1 GiB copy at the end of the probe (FETCH_SIZE x2.000, WRITE_SIZE x1.000); see
+# profiles/*_hbm_traffic.md.  Not measured live.  "dkdv" is the dK/dV stage as timed here:
+# the dK/dV kernel plus the reduction of split tiles.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg2_grpo_single_prompt_tree": {"fwd": 4.57e8, "dq": 6.50e8, "dkdv": 3.52e9},
+    "cfg2_grpo_single_prompt_tree": {"fwd": 4.56e8, "dq": 6.94e8, "dkdv": 3.55e9},
+    "cfg4_deep_long_context_tree": {"fwd": 5.24e10, "dq": 5.82e10, "dkdv": 4.20e11},
 }
 
 
@@ -200,6 +203,10 @@ def main():
     ap.add_argument("--others", type=str, default="3,4,5", help="configs reported as extra objects ('' = none)")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="no timing: two steps of --config, then a plain 1 GiB device copy; the program "
+                         "to run under `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` (the copy "
+                         "calibrates the counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
@@ -214,6 +221,20 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     torch.cuda.set_device(0)
+
+    if args.traffic_probe:
+        parent, seg, meta = config_tree(args.config)
+        r = Runner(parent, seg, config_heads(args.config), meta["tensor_seed"])
+        for _ in range(2):
+            r.step().destroy()
+            torch.cuda.synchronize()
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)      # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        print(json.dumps({"traffic_probe": WORKLOAD_NAMES[args.config], "steps": 2, "copy_bytes": 1 << 30}))
+        return
 
     def leaf_lengths(parent, seg):
         tree = dta.tree_build(parent, seg)
