@@ -400,3 +400,111 @@ def test_tree_token_identity_over_dfs_leaf_order():
                 lcp += 1
             total += len(b) - lcp
         assert total == int(seg.sum())
+
+
+# ------------------------------------------- push / pop executor (oracle C)
+from oracle import dfs_executor as X
+
+
+def test_executor_equals_rollout_expansion_and_counts_its_steps():
+    """The stack-based push/pop traversal (a third formulation) must give the
+    tensors of the rollout-expansion oracle; every node is forwarded once and
+    popped once, a child's FWD follows its parent's and its BWD precedes it,
+    and the stack never holds more than the longest root-to-leaf path."""
+    rng = np.random.default_rng(71)
+    for n_nodes, max_len, n_roots in ((1, 5, 1), (9, 6, 1), (14, 5, 3)):
+        parent, seg = random_tree(rng, n_nodes, max_len, n_roots=n_roots)
+        T = int(seg.sum())
+        q, k, v, do = _inputs(T, 4, 2, 8, seed=40 + n_nodes)
+        scale = 0.3
+        r = X.vanilla_dta(parent, seg, q, k, v, do, scale)
+        O, LSE = A.forward(parent, seg, q, k, v, scale)
+        dQ, dK, dV = A.backward(parent, seg, q, k, v, do, scale)
+        for name, ref in (("O", O), ("LSE", LSE), ("dQ", dQ), ("dK", dK), ("dV", dV)):
+            assert np.abs(r[name] - ref).max() < 1e-11, name
+        fwd = [t[1] for t in r["trace"] if t[0] == "FWD"]
+        bwd = [t[1] for t in r["trace"] if t[0] == "BWD"]
+        assert sorted(fwd) == sorted(bwd) == list(range(n_nodes))
+        assert fwd == L.preorder(parent)                       # pushes happen in DFS preorder
+        pos_f = {u: i for i, t in enumerate(r["trace"]) for u in [t[1]] if t[0] == "FWD"}
+        pos_b = {u: i for i, t in enumerate(r["trace"]) for u in [t[1]] if t[0] == "BWD"}
+        for u in range(n_nodes):
+            assert pos_f[u] < pos_b[u]
+            if parent[u] >= 0:
+                assert pos_f[int(parent[u])] < pos_f[u] and pos_b[u] < pos_b[int(parent[u])]
+        assert r["peak_stack"] == max(len(p) for p in L.rollout_token_paths(parent, seg))
+
+
+def test_segment_primitives_on_a_chain_are_rows_of_torch_sdpa():
+    """FWD of the last segment of a chain = the last rows of ordinary causal
+    attention over the whole chain; BWD with dO on those rows only = torch's
+    autograd of the same (outside library routine)."""
+    L_, m, d = 23, 7, 16
+    rng = np.random.default_rng(5)
+    q = rng.standard_normal((L_, d)); k = rng.standard_normal((L_, d)); v = rng.standard_normal((L_, d))
+    do = rng.standard_normal((m, d))
+    scale = 1.0 / math.sqrt(d)
+    o, lse, p = X.fwd_segment(q[L_ - m:], k, v, scale)
+    tq = torch.tensor(q, requires_grad=True); tk = torch.tensor(k, requires_grad=True)
+    tv = torch.tensor(v, requires_grad=True)
+    out = torch.nn.functional.scaled_dot_product_attention(tq[None, None], tk[None, None], tv[None, None],
+                                                           is_causal=True, scale=scale)[0, 0]
+    assert np.abs(o - out.detach().numpy()[L_ - m:]).max() < 1e-12
+    s = scale * tq.detach() @ tk.detach().T
+    s = s.masked_fill(torch.triu(torch.ones(L_, L_, dtype=torch.bool), 1), -float("inf"))
+    assert np.abs(lse - torch.logsumexp(s, -1).numpy()[L_ - m:]).max() < 1e-12
+    full_do = torch.zeros(L_, d, dtype=torch.float64)
+    full_do[L_ - m:] = torch.tensor(do)
+    out.backward(full_do)
+    dq, dk, dv = X.bwd_segment(q[L_ - m:], k, v, o, p, do, scale)
+    assert np.abs(dq - tq.grad.numpy()[L_ - m:]).max() < 1e-11
+    assert np.abs(tq.grad.numpy()[:L_ - m]).max() == 0.0
+    assert np.abs(dk - tk.grad.numpy()).max() < 1e-11
+    assert np.abs(dv - tv.grad.numpy()).max() < 1e-11
+
+
+def test_segment_backward_against_central_finite_differences():
+    rng = np.random.default_rng(8)
+    L_, m, d, scale = 9, 4, 5, 0.37
+    q = rng.standard_normal((m, d)); k = rng.standard_normal((L_, d)); v = rng.standard_normal((L_, d))
+    do = rng.standard_normal((m, d))
+    f = lambda: float((X.fwd_segment(q, k, v, scale)[0] * do).sum())
+    o, _, p = X.fwd_segment(q, k, v, scale)
+    dq, dk, dv = X.bwd_segment(q, k, v, o, p, do, scale)
+    eps = 1e-5
+    for arr, grad in ((q, dq), (k, dk), (v, dv)):
+        for i in np.ndindex(arr.shape):
+            old = arr[i]
+            arr[i] = old + eps; fp = f()
+            arr[i] = old - eps; fm = f()
+            arr[i] = old
+            assert abs((fp - fm) / (2 * eps) - grad[i]) < 1e-8
+
+
+def test_chunked_pops_change_nothing_and_run_last_chunk_first():
+    """Pop_ByChunk: boundaries evenly spaced and at most `block` apart, chunks
+    run from the last to the first, each with a recomputing FWD; the tensors do
+    not depend on the block size."""
+    assert X.chunk_boundaries(10, 30, 0) == [10, 30]
+    assert X.chunk_boundaries(10, 30, 20) == [10, 30]
+    for lo, hi, block in ((0, 17, 4), (5, 6, 1), (3, 103, 7), (0, 64, 16)):
+        b = X.chunk_boundaries(lo, hi, block)
+        gaps = np.diff(b)
+        assert b[0] == lo and b[-1] == hi and gaps.min() >= 1 and gaps.max() <= block
+        assert len(b) - 1 == -(-(hi - lo) // block) and gaps.max() - gaps.min() <= 1
+    rng = np.random.default_rng(72)
+    parent, seg = random_tree(rng, 8, 11)
+    T = int(seg.sum())
+    q, k, v, do = _inputs(T, 4, 2, 8, seed=77)
+    base = X.vanilla_dta(parent, seg, q, k, v, do, 0.25)
+    for block in (1, 3, 4):
+        r = X.vanilla_dta(parent, seg, q, k, v, do, 0.25, chunk_block=block)
+        for name in ("O", "LSE", "dQ", "dK", "dV"):
+            assert np.abs(r[name] - base[name]).max() < 1e-12, (block, name)
+        per_node = {}
+        for tag, node, t0, t1 in r["trace"]:
+            if tag == "BWD":
+                per_node.setdefault(node, []).append((t0, t1))
+        for node, chunks in per_node.items():
+            assert all(a[0] == b[1] for a, b in zip(chunks, chunks[1:]))     # right to left, contiguous
+            assert max(t1 - t0 for t0, t1 in chunks) <= block
