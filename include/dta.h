@@ -194,6 +194,49 @@ int dta_tree_attn_bwd_stages(dta_tree_t* tree, const dta_attn_params_t* params, 
                              const void* d_o, void* dq, void* dk, void* dv, void* workspace,
                              size_t workspace_bytes, void* hip_stream, uint32_t stage_mask);
 
+/*
+ * Segment calls: the attention inside the paper's FWD(l_start -> l_end) and BWD
+ * primitives (pseudocode appendix, notation block), which its push / pop
+ * traversal issues once per token segment (section 3.1; vanilla algorithm), and
+ * once per chunk of a segment in the chunked pops of the optimised algorithm
+ * (Pop_ByChunk).
+ *
+ *   [t_begin, t_end) : packed token rows of the call; non-empty and inside ONE
+ *                      node's segment (a whole segment or a chunk of it), else
+ *                      DTA_ERR_INVALID_ARG.
+ *
+ * dta_tree_attn_fwd_segment computes o and lse for these rows only.  The rows'
+ * queries see the keys/values on their root path: the segments of the node's
+ * ancestors, the node's tokens before the row, and the row itself.  Tensors are
+ * the full packed [T, H, head_dim] tensors of dta_tree_attn_fwd (same layout,
+ * alignment and ownership); of q, o, lse only the rows are read / written, of
+ * k, v only rows on the root path up to t_end are read, so nothing else needs
+ * to be valid yet (this is the paper's active stack: only the current path).
+ *
+ * dta_tree_attn_bwd_segment backpropagates the rows' attached gradient d_o
+ * (rows [t_begin, t_end) of the per-tree-token dO): it writes dq for the rows
+ * (final: a row's dQ depends on nothing else) and ADDS the rows' contributions
+ * to dK and dV of every key they see into dk_acc / dv_acc, fp32
+ * [T, n_kv_heads, head_dim] accumulators owned by the caller (zeroed by the
+ * caller before the first call; rows of keys the call does not see are not
+ * touched).  When all descendants of a key's node and the later rows of its own
+ * segment have been popped, the key's accumulated gradient is final: running
+ * the calls in the paper's pop order reproduces dta_tree_attn_bwd.  Calls
+ * that add into the same accumulators must not overlap (same stream, or
+ * ordered by events); within a call every key has one owner, so results are
+ * bit-reproducible for a fixed sequence of calls.  o, lse: the forward results
+ * of the rows.  workspace: as for dta_tree_attn_bwd (same size).
+ */
+int dta_tree_attn_fwd_segment(dta_tree_t* tree, const dta_attn_params_t* params, int64_t t_begin,
+                              int64_t t_end, const void* q, const void* k, const void* v, void* o,
+                              float* lse, void* workspace, size_t workspace_bytes,
+                              void* hip_stream);
+int dta_tree_attn_bwd_segment(dta_tree_t* tree, const dta_attn_params_t* params, int64_t t_begin,
+                              int64_t t_end, const void* q, const void* k, const void* v,
+                              const void* o, const float* lse, const void* d_o, void* dq,
+                              float* dk_acc, float* dv_acc, void* workspace,
+                              size_t workspace_bytes, void* hip_stream);
+
 /* Static, human-readable name of a status code. */
 const char* dta_status_string(int status);
 

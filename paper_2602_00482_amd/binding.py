@@ -19,7 +19,8 @@ F32, BF16 = 0, 1
 exported_symbols = [
     "dta_tree_build", "dta_tree_info", "dta_tree_layout", "dta_tree_schedule_info",
     "dta_tree_destroy", "dta_tree_attn_workspace_bytes", "dta_tree_attn_prepare",
-    "dta_tree_attn_fwd", "dta_tree_attn_bwd", "dta_tree_attn_bwd_stages", "dta_status_string",
+    "dta_tree_attn_fwd", "dta_tree_attn_bwd", "dta_tree_attn_bwd_stages",
+    "dta_tree_attn_fwd_segment", "dta_tree_attn_bwd_segment", "dta_status_string",
 ]
 
 
@@ -84,6 +85,12 @@ def load_library():
     lib.dta_tree_attn_bwd.restype = C.c_int
     lib.dta_tree_attn_bwd_stages.argtypes = [vp, C.POINTER(AttnParams)] + [vp] * 9 + [vp, C.c_size_t, vp, C.c_uint32]
     lib.dta_tree_attn_bwd_stages.restype = C.c_int
+    lib.dta_tree_attn_fwd_segment.argtypes = ([vp, C.POINTER(AttnParams), C.c_int64, C.c_int64] + [vp] * 5 +
+                                              [vp, C.c_size_t, vp])
+    lib.dta_tree_attn_fwd_segment.restype = C.c_int
+    lib.dta_tree_attn_bwd_segment.argtypes = ([vp, C.POINTER(AttnParams), C.c_int64, C.c_int64] + [vp] * 9 +
+                                              [vp, C.c_size_t, vp])
+    lib.dta_tree_attn_bwd_segment.restype = C.c_int
     lib.dta_status_string.argtypes = [C.c_int]
     lib.dta_status_string.restype = C.c_char_p
     _lib = lib
@@ -236,3 +243,44 @@ def tree_attn_bwd(tree: Tree, params: AttnParams, q, k, v, o, lse, d_o, dq=None,
     else:
         _check(lib.dta_tree_attn_bwd_stages(*args, int(stages)), "dta_tree_attn_bwd_stages")
     return dq, dk, dv
+
+
+def tree_attn_fwd_segment(tree: Tree, params: AttnParams, t_begin: int, t_end: int, q, k, v, o, lse):
+    """dta_tree_attn_fwd_segment on torch's current stream: fills rows
+    [t_begin, t_end) of the full-size o and lse."""
+    import torch
+    dt = torch.float32 if params.dtype == F32 else torch.bfloat16
+    T = q.shape[0]
+    _check_tensor(q, "q", (T, params.n_q_heads, params.head_dim), dt)
+    _check_tensor(k, "k", (T, params.n_kv_heads, params.head_dim), dt)
+    _check_tensor(v, "v", (T, params.n_kv_heads, params.head_dim), dt)
+    _check_tensor(o, "o", q.shape, dt)
+    _check_tensor(lse, "lse", (T, params.n_q_heads), torch.float32)
+    st = load_library().dta_tree_attn_fwd_segment(tree.handle, C.byref(params), int(t_begin), int(t_end),
+                                                  _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse),
+                                                  C.c_void_p(0), 0, _stream())
+    _check(st, "dta_tree_attn_fwd_segment")
+
+
+def tree_attn_bwd_segment(tree: Tree, params: AttnParams, t_begin: int, t_end: int, q, k, v, o, lse, d_o,
+                          dq, dk_acc, dv_acc, workspace):
+    """dta_tree_attn_bwd_segment on torch's current stream: writes rows
+    [t_begin, t_end) of dq and adds into the fp32 accumulators dk_acc, dv_acc."""
+    import torch
+    dt = torch.float32 if params.dtype == F32 else torch.bfloat16
+    T = q.shape[0]
+    _check_tensor(q, "q", (T, params.n_q_heads, params.head_dim), dt)
+    _check_tensor(k, "k", (T, params.n_kv_heads, params.head_dim), dt)
+    _check_tensor(v, "v", (T, params.n_kv_heads, params.head_dim), dt)
+    _check_tensor(o, "o", q.shape, dt)
+    _check_tensor(d_o, "d_o", q.shape, dt)
+    _check_tensor(lse, "lse", (T, params.n_q_heads), torch.float32)
+    _check_tensor(dq, "dq", q.shape, dt)
+    _check_tensor(dk_acc, "dk_acc", k.shape, torch.float32)
+    _check_tensor(dv_acc, "dv_acc", v.shape, torch.float32)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    st = load_library().dta_tree_attn_bwd_segment(tree.handle, C.byref(params), int(t_begin), int(t_end),
+                                                  _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o),
+                                                  _ptr(dq), _ptr(dk_acc), _ptr(dv_acc), _ptr(workspace),
+                                                  ws_bytes, _stream())
+    _check(st, "dta_tree_attn_bwd_segment")

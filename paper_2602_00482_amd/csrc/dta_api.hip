@@ -130,7 +130,7 @@ Part part_of(const std::vector<T>& v, T** dst) {
 // device.  Takes the tree lock; blocking (on the upload only) on first use, a
 // no-op afterwards.
 int ensure_device(dta_tree* tree, const dta::TileChoice& tc, const dta_attn_params_t* p,
-                  dta::Schedule** out) {
+                  dta::Schedule** out, int64_t t_begin = -1, int64_t t_end = -1) {
   std::lock_guard<std::mutex> lock(tree->mu);
   int dev = -1;
   if (hipGetDevice(&dev) != hipSuccess) {
@@ -140,7 +140,10 @@ int ensure_device(dta_tree* tree, const dta::TileChoice& tc, const dta_attn_para
   }
   dta::Schedule* s;
   try {
-    s = &dta::get_schedule(tree, tc.bm, tc.bn, p->n_kv_heads, p->n_q_heads / p->n_kv_heads);
+    s = t_begin < 0
+            ? &dta::get_schedule(tree, tc.bm, tc.bn, p->n_kv_heads, p->n_q_heads / p->n_kv_heads)
+            : &dta::get_segment_schedule(tree, tc.bm, tc.bn, p->n_kv_heads,
+                                         p->n_q_heads / p->n_kv_heads, t_begin, t_end);
   } catch (const std::bad_alloc&) {
     return DTA_ERR_ALLOC;
   }
@@ -220,6 +223,7 @@ void dta_tree_destroy(dta_tree_t* tree) {
   if (!tree) return;
   release_blob(tree, tree->d_token_kend, tree->kend_device);
   for (auto& kv : tree->schedules) release_blob(tree, kv.second.d_blob, kv.second.device);
+  for (auto& kv : tree->segment_schedules) release_blob(tree, kv.second.d_blob, kv.second.device);
   if (tree->last_use) (void)hipEventDestroy((hipEvent_t)tree->last_use);
   delete tree;
 }
@@ -266,6 +270,8 @@ int dta_tree_attn_fwd(dta_tree_t* tree, const dta_attn_params_t* params, const v
   a.v = v;
   a.o_out = o;
   a.lse_out = lse;
+  a.row_begin = 0;
+  a.row_end = tree->info.n_tokens;
   a.stream = hip_stream;
   return mark_use(tree, hip_stream,
                   params->dtype == DTA_F32 ? dta::launch_fwd_f32(a) : dta::launch_fwd_bf16(a));
@@ -310,6 +316,8 @@ int dta_tree_attn_bwd_stages(dta_tree_t* tree, const dta_attn_params_t* params, 
   a.lse2 = (float*)((char*)workspace + delta_bytes(tree, params));
   a.partial = (float*)((char*)workspace + 2 * delta_bytes(tree, params));
   a.stages = stage_mask;
+  a.row_begin = 0;
+  a.row_end = tree->info.n_tokens;
   a.stream = hip_stream;
   return mark_use(tree, hip_stream,
                   params->dtype == DTA_F32 ? dta::launch_bwd_f32(a) : dta::launch_bwd_bf16(a));
@@ -321,6 +329,93 @@ int dta_tree_attn_bwd(dta_tree_t* tree, const dta_attn_params_t* params, const v
                       size_t workspace_bytes, void* hip_stream) {
   return dta_tree_attn_bwd_stages(tree, params, q, k, v, o, lse, d_o, dq, dk, dv, workspace,
                                   workspace_bytes, hip_stream, DTA_BWD_ALL);
+}
+
+// rows [t_begin, t_end) must be non-empty and lie inside one node's segment
+static int check_segment(const dta_tree* tree, int64_t t_begin, int64_t t_end) {
+  if (t_begin < 0 || t_end <= t_begin || t_end > tree->info.n_tokens) return DTA_ERR_INVALID_ARG;
+  if (tree->token_node[(size_t)t_begin] != tree->token_node[(size_t)(t_end - 1)])
+    return DTA_ERR_INVALID_ARG;
+  return DTA_OK;
+}
+
+int dta_tree_attn_fwd_segment(dta_tree_t* tree, const dta_attn_params_t* params, int64_t t_begin,
+                              int64_t t_end, const void* q, const void* k, const void* v, void* o,
+                              float* lse, void* workspace, size_t workspace_bytes,
+                              void* hip_stream) {
+  (void)workspace;
+  (void)workspace_bytes;
+  if (!tree || !params) return DTA_ERR_INVALID_ARG;
+  dta::TileChoice tc;
+  int st = dta::choose_tiles(params, &tc);
+  if (st != DTA_OK) return st;
+  if ((st = check_segment(tree, t_begin, t_end)) != DTA_OK) return st;
+  if (!q || !k || !v || !o || !lse) return DTA_ERR_INVALID_ARG;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse))
+    return DTA_ERR_INVALID_ARG;
+  dta::Schedule* s = nullptr;
+  if ((st = ensure_device(tree, tc, params, &s, t_begin, t_end)) != DTA_OK) return st;
+  dta::LaunchArgs a{};
+  a.tree = tree;
+  a.sched = s;
+  a.d_kend = tree->d_token_kend;
+  a.p = *params;
+  a.tc = tc;
+  a.q = q;
+  a.k = k;
+  a.v = v;
+  a.o_out = o;
+  a.lse_out = lse;
+  a.row_begin = t_begin;
+  a.row_end = t_end;
+  a.stream = hip_stream;
+  return mark_use(tree, hip_stream,
+                  params->dtype == DTA_F32 ? dta::launch_fwd_f32(a) : dta::launch_fwd_bf16(a));
+}
+
+int dta_tree_attn_bwd_segment(dta_tree_t* tree, const dta_attn_params_t* params, int64_t t_begin,
+                              int64_t t_end, const void* q, const void* k, const void* v,
+                              const void* o, const float* lse, const void* d_o, void* dq,
+                              float* dk_acc, float* dv_acc, void* workspace,
+                              size_t workspace_bytes, void* hip_stream) {
+  if (!tree || !params) return DTA_ERR_INVALID_ARG;
+  dta::TileChoice tc;
+  int st = dta::choose_tiles(params, &tc);
+  if (st != DTA_OK) return st;
+  if ((st = check_segment(tree, t_begin, t_end)) != DTA_OK) return st;
+  if (!q || !k || !v || !o || !lse || !d_o || !dq || !dk_acc || !dv_acc) return DTA_ERR_INVALID_ARG;
+  if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o) || misaligned(lse) ||
+      misaligned(d_o) || misaligned(dq) || misaligned(dk_acc) || misaligned(dv_acc))
+    return DTA_ERR_INVALID_ARG;
+  if (!workspace || workspace_bytes < bwd_workspace_bytes(tree, tc, params) ||
+      ((uintptr_t)workspace & 255u))
+    return DTA_ERR_WORKSPACE;
+  dta::Schedule* s = nullptr;
+  if ((st = ensure_device(tree, tc, params, &s, t_begin, t_end)) != DTA_OK) return st;
+  dta::LaunchArgs a{};
+  a.tree = tree;
+  a.sched = s;
+  a.d_kend = tree->d_token_kend;
+  a.p = *params;
+  a.tc = tc;
+  a.q = q;
+  a.k = k;
+  a.v = v;
+  a.o = o;
+  a.d_o = d_o;
+  a.lse_in = lse;
+  a.dq = dq;
+  a.dk_acc = dk_acc;
+  a.dv_acc = dv_acc;
+  a.delta = (float*)workspace;
+  a.lse2 = (float*)((char*)workspace + delta_bytes(tree, params));
+  a.partial = (float*)((char*)workspace + 2 * delta_bytes(tree, params));
+  a.stages = DTA_BWD_ALL;
+  a.row_begin = t_begin;
+  a.row_end = t_end;
+  a.stream = hip_stream;
+  return mark_use(tree, hip_stream,
+                  params->dtype == DTA_F32 ? dta::launch_bwd_f32(a) : dta::launch_bwd_bf16(a));
 }
 
 }  // extern "C"

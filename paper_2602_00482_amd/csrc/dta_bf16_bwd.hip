@@ -275,8 +275,8 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, const uint16_t* __restrict__ d_o,
     const float* __restrict__ neg_lse_s, const float* __restrict__ neg_delta,
-    uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, float* __restrict__ partial, int Hq,
-    int Hkv, float scale) {
+    uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, float* __restrict__ partial,
+    float* __restrict__ dk_acc, float* __restrict__ dv_acc, int Hq, int Hkv, float scale) {
   // One object, so that every tile read is "per-lane base + compile-time offset".
   // The last k-steps of this wave's K and V operands (kStashK and kStashV of the
   // 8) live in LDS instead of registers, and so do the per-lane mask bounds
@@ -343,13 +343,13 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
   // same 64-row chunks at the same time and find them in L2.  Step `it` lives
   // in buffer it & 1 and is copied global -> LDS one iteration ahead of its use
   // (this item covers iterations [it_begin, it_end) of the tile's walk)
-  const int n_chunks = (tile.q_end - tile.k0 + kBQ - 1) / kBQ;
+  const int n_chunks = (tile.q_end - tile.q_begin + kBQ - 1) / kBQ;
   const int total = tile.it_end;
   auto issue = [&](int it, int b) {
     const int cq = it / G, hsub = it - cq * G;
     const int ch = n_chunks - 1 - cq;
     const int h = g * G + hsub;
-    const int r0 = tile.k0 + ch * kBQ;
+    const int r0 = tile.q_begin + ch * kBQ;
     const int nv = min(kBQ, tile.q_end - r0);
     if (__builtin_amdgcn_readfirstlane(w) == 0) {   // stat is indexed by matrix position
       const uint32_t off = (uint32_t)min(row_of_pos(l), nv - 1) * (uint32_t)Hq;
@@ -369,7 +369,7 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
     __syncthreads();   // chunk `buf` has landed; everyone is done with the other buffer
     if (it + 1 < total) issue(it + 1, buf ^ 1);
     const int ch = n_chunks - 1 - it / G;
-    const int r0 = tile.k0 + ch * kBQ;
+    const int r0 = tile.q_begin + ch * kBQ;
     const int nv = min(kBQ, tile.q_end - r0);
     const bool need_mask = !(r0 >= tile.k1 && r0 + kBQ <= tile.q_full_end);
     const uint16_t* Qt = sm.Q[buf] + rlo;
@@ -510,6 +510,26 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
         *reinterpret_cast<f32x4*>(pk + 32 * dmb + 8 * v4) = rk;
         *reinterpret_cast<f32x4*>(pv + 32 * dmb + 8 * v4) = rv;
       }
+  } else if (dk_acc != nullptr) {
+    // segment call: this block is the only one that owns these keys in this
+    // launch; add to the caller's fp32 accumulators
+    if (kcol < tile.k1) {
+      const size_t base = ((size_t)kcol * Hkv + g) * kHeadDim + 4 * hh;
+#pragma unroll
+      for (int dmb = 0; dmb < 4; ++dmb)
+#pragma unroll
+        for (int v4 = 0; v4 < 4; ++v4) {
+          f32x4 rk = *reinterpret_cast<const f32x4*>(dk_acc + base + 32 * dmb + 8 * v4);
+          f32x4 rv = *reinterpret_cast<const f32x4*>(dv_acc + base + 32 * dmb + 8 * v4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            rk[e] += dK[dmb][4 * v4 + e] * scale;
+            rv[e] += dV[dmb][4 * v4 + e];
+          }
+          *reinterpret_cast<f32x4*>(dk_acc + base + 32 * dmb + 8 * v4) = rk;
+          *reinterpret_cast<f32x4*>(dv_acc + base + 32 * dmb + 8 * v4) = rv;
+        }
+    }
   } else if (kcol < tile.k1) {
     const size_t base = ((size_t)kcol * Hkv + g) * kHeadDim + 4 * hh;
 #pragma unroll
@@ -566,14 +586,16 @@ __global__ __launch_bounds__(256) void dkdv_reduce_kernel(const KvReduce* __rest
 int launch_bwd_bf16(const LaunchArgs& a) {
   hipStream_t st = (hipStream_t)a.stream;
   clear_hip_error();
-  const size_t rows = (size_t)a.tree->info.n_tokens * a.p.n_q_heads;
+  // rows of (token, q head) the call covers: all of them, or one segment's
+  const size_t row0 = (size_t)a.row_begin * a.p.n_q_heads;
+  const size_t rows = (size_t)(a.row_end - a.row_begin) * a.p.n_q_heads;
   const size_t qblocks = a.sched->q_tiles.size() * (size_t)a.p.n_kv_heads * (size_t)a.tc.hblocks;
   const size_t kblocks = a.sched->kv_items.size() * (size_t)a.p.n_kv_heads;
   if (qblocks == 0 || qblocks > 0x7fffffffu || kblocks > 0x7fffffffu) return DTA_ERR_UNSUPPORTED;
   if (a.stages & DTA_BWD_DELTA) {
     delta_bf16_kernel<<<(unsigned)((rows + 15) / 16), 256, 0, st>>>(
-        (const uint16_t*)a.o, (const uint16_t*)a.d_o, a.lse_in, a.delta, a.lse2,
-        1.f / a.p.softmax_scale, rows);
+        (const uint16_t*)a.o + row0 * kHeadDim, (const uint16_t*)a.d_o + row0 * kHeadDim,
+        a.lse_in + row0, a.delta + row0, a.lse2 + row0, 1.f / a.p.softmax_scale, rows);
     { int ls = launch_status(__func__); if (ls != DTA_OK) return ls; }
   }
   if (a.stages & DTA_BWD_DQ) {
@@ -587,7 +609,8 @@ int launch_bwd_bf16(const LaunchArgs& a) {
     dkdv_bf16_kernel<<<(unsigned)kblocks, kKvThreads, 0, st>>>(
         a.sched->d_kv_items, a.d_kend, (const uint16_t*)a.q, (const uint16_t*)a.k,
         (const uint16_t*)a.v, (const uint16_t*)a.d_o, a.lse2, a.delta, (uint16_t*)a.dk,
-        (uint16_t*)a.dv, a.partial, a.p.n_q_heads, a.p.n_kv_heads, a.p.softmax_scale);
+        (uint16_t*)a.dv, a.partial, a.dk_acc, a.dv_acc, a.p.n_q_heads, a.p.n_kv_heads,
+        a.p.softmax_scale);
     { int ls = launch_status(__func__); if (ls != DTA_OK) return ls; }
     if (!a.sched->kv_reduce.empty()) {
       dkdv_reduce_kernel<<<(unsigned)(a.sched->kv_reduce.size() * a.p.n_kv_heads * 8), 256, 0, st>>>(

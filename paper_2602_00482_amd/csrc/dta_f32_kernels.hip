@@ -200,7 +200,8 @@ __global__ __launch_bounds__(256) void dkdv_f32_kernel(const KvTile* __restrict_
                                                        const float* __restrict__ lse,
                                                        const float* __restrict__ delta,
                                                        float* __restrict__ dk, float* __restrict__ dv,
-                                                       int Hq, int Hkv, float scale) {
+                                                       int accumulate, int Hq, int Hkv,
+                                                       float scale) {
   constexpr int DS = D / kLanes;
   __shared__ float Qs[kChunk][D];
   __shared__ float dOs[kChunk][D];
@@ -223,7 +224,7 @@ __global__ __launch_bounds__(256) void dkdv_f32_kernel(const KvTile* __restrict_
 
   for (int hh = 0; hh < G; ++hh) {
     const int h = g * G + hh;
-    for (int c0 = tile.k0; c0 < tile.q_end; c0 += kChunk) {
+    for (int c0 = tile.q_begin; c0 < tile.q_end; c0 += kChunk) {
       const int n = min(kChunk, tile.q_end - c0);
       __syncthreads();
       stage_rows<D>(Qs, q + (size_t)c0 * q_stride + (size_t)h * D, q_stride, n);
@@ -257,7 +258,12 @@ __global__ __launch_bounds__(256) void dkdv_f32_kernel(const KvTile* __restrict_
   if (valid) {
     const size_t base = ((size_t)kk * Hkv + g) * D + j * DS;
 #pragma unroll
-    for (int i = 0; i < DS; ++i) { dk[base + i] = dka[i] * scale; dv[base + i] = dva[i]; }
+    for (int i = 0; i < DS; ++i) {
+      // a segment call adds to the caller's accumulators (this lane group is the
+      // only owner of the key in the launch)
+      dk[base + i] = (accumulate ? dk[base + i] : 0.f) + dka[i] * scale;
+      dv[base + i] = (accumulate ? dv[base + i] : 0.f) + dva[i];
+    }
   }
 }
 
@@ -277,10 +283,11 @@ template <int D>
 int bwd_impl(const LaunchArgs& a) {
   hipStream_t st = (hipStream_t)a.stream;
   clear_hip_error();
-  const size_t rows = (size_t)a.tree->info.n_tokens * a.p.n_q_heads;
+  const size_t row0 = (size_t)a.row_begin * a.p.n_q_heads;
+  const size_t rows = (size_t)(a.row_end - a.row_begin) * a.p.n_q_heads;
   if (a.stages & DTA_BWD_DELTA) {
     delta_f32_kernel<D><<<(unsigned)((rows + kRows - 1) / kRows), 256, 0, st>>>(
-        (const float*)a.o, (const float*)a.d_o, a.delta, rows);
+        (const float*)a.o + row0 * D, (const float*)a.d_o + row0 * D, a.delta + row0, rows);
     { int ls = launch_status(__func__); if (ls != DTA_OK) return ls; }
   }
   if (a.stages & DTA_BWD_DQ) {
@@ -295,9 +302,10 @@ int bwd_impl(const LaunchArgs& a) {
     dim3 gk((unsigned)a.sched->kv_tiles.size(), (unsigned)a.p.n_kv_heads);
     dkdv_f32_kernel<D><<<gk, 256, 0, st>>>(a.sched->d_kv_tiles, a.d_kend, (const float*)a.q,
                                            (const float*)a.k, (const float*)a.v,
-                                           (const float*)a.d_o, a.lse_in, a.delta, (float*)a.dk,
-                                           (float*)a.dv, a.p.n_q_heads, a.p.n_kv_heads,
-                                           a.p.softmax_scale);
+                                           (const float*)a.d_o, a.lse_in, a.delta,
+                                           a.dk_acc ? a.dk_acc : (float*)a.dk,
+                                           a.dk_acc ? a.dv_acc : (float*)a.dv, a.dk_acc != nullptr,
+                                           a.p.n_q_heads, a.p.n_kv_heads, a.p.softmax_scale);
     { int ls = launch_status(__func__); if (ls != DTA_OK) return ls; }
   }
   return DTA_OK;

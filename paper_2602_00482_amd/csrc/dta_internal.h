@@ -4,6 +4,7 @@
 
 #include <cstddef>
 #include <cstdint>
+#include <array>
 #include <map>
 #include <mutex>
 #include <vector>
@@ -29,13 +30,18 @@ struct KeySeg {
   int32_t pad;
 };
 
-// One dK/dV work item: BN consecutive packed keys [k0, k1).  The queries that
-// see at least one of them are exactly [k0, q_end); rows in [k1, q_full_end)
-// see all of them, every other row needs the visibility mask.
+// One dK/dV work item: BN consecutive packed keys [k0, k1).  The queries the
+// item walks are [q_begin, q_end): for a whole-tree launch q_begin = k0 and
+// these are exactly the rows that see at least one of the keys; a segment
+// launch narrows the walk to the segment's rows.  Rows in
+// [max(k1, q_begin), q_full_end) see all of the keys, every other row needs the
+// visibility mask.
 struct KvTile {
   int32_t k0, k1;
   int32_t q_end;
   int32_t q_full_end;
+  int32_t q_begin;
+  int32_t pad[3];
 };
 
 // One launch unit of the bf16 dK/dV kernel: key tile [k0, k1) and a slice
@@ -50,7 +56,7 @@ struct KvItem {
   int32_t q_end, q_full_end;
   int32_t it_begin, it_end;
   int32_t slot;
-  int32_t pad;
+  int32_t q_begin;   // first row of the walk (see KvTile)
 };
 
 // A split key tile: its partial sums live in slots [first_slot, first_slot + nparts).
@@ -96,6 +102,8 @@ struct dta_tree {
   dta_tree_info_t info{};
   // schedules keyed by (bm, bn, kv heads, group size)
   std::map<uint64_t, dta::Schedule> schedules;
+  // schedules of segment calls, keyed by (tile configuration, t_begin, t_end)
+  std::map<std::array<uint64_t, 3>, dta::Schedule> segment_schedules;
   int32_t* d_token_kend = nullptr;
   int kend_device = -1;
   void* last_use = nullptr;   // hipEvent_t recorded after every launch that reads the device copies
@@ -107,6 +115,11 @@ namespace dta {
 
 // Host: build (or fetch) the schedule for tile sizes (bm, bn).
 Schedule& get_schedule(dta_tree* tree, int bm, int bn, int hkv, int group);
+// Same for a segment call on rows [t_begin, t_end), which must lie inside one
+// node's segment (checked by the caller): query tiles over the rows, key tiles
+// over the root path up to t_end, no split items.
+Schedule& get_segment_schedule(dta_tree* tree, int bm, int bn, int hkv, int group,
+                               int64_t t_begin, int64_t t_end);
 // Bytes of fp32 partial dK/dV sums the split items of a schedule need.
 size_t partial_bytes(const Schedule& s);
 
@@ -133,6 +146,10 @@ struct LaunchArgs {
   float* delta;  // workspace: D[t,h] = dO.O
   float* lse2;   // workspace (bf16 path): -lse / softmax_scale, written with delta (there: -D)
   float* partial;  // workspace: fp32 partial dK/dV of split key tiles
+  // segment calls: rows [row_begin, row_end) only, and dK/dV are ADDED to these
+  // fp32 [T,Hkv,d] accumulators instead of written to dk/dv (null otherwise)
+  int64_t row_begin, row_end;
+  float *dk_acc, *dv_acc;
   uint32_t stages;  // backward stages to launch (DTA_BWD_*)
   void* stream;
 };

@@ -229,7 +229,7 @@ Schedule& get_schedule(dta_tree* tree, int bm, int bn, int hkv, int group) {
       mx = std::max(mx, tree->token_kend[(size_t)k]);
       mn = std::min(mn, tree->token_kend[(size_t)k]);
     }
-    s.kv_tiles.push_back(KvTile{(int32_t)k0, (int32_t)k1, mx, mn});
+    s.kv_tiles.push_back(KvTile{(int32_t)k0, (int32_t)k1, mx, mn, (int32_t)k0, {0, 0, 0}});
     cost.push_back(mx - k0);
     s.bwd_tile_pairs += (int64_t)(mx - k0) * bn;
   }
@@ -263,7 +263,8 @@ Schedule& get_schedule(dta_tree* tree, int bm, int bn, int hkv, int group) {
       if (nparts > 1) s.kv_reduce.push_back(KvReduce{t.k0, t.k1, (int32_t)s.n_slots, (int32_t)nparts});
       for (int64_t p = 0; p < nparts; ++p) {
         KvItem it{t.k0, t.k1, t.q_end, t.q_full_end, (int32_t)(iters * p / nparts),
-                  (int32_t)(iters * (p + 1) / nparts), nparts > 1 ? (int32_t)(s.n_slots + p) : -1, 0};
+                  (int32_t)(iters * (p + 1) / nparts), nparts > 1 ? (int32_t)(s.n_slots + p) : -1,
+                  t.q_begin};
         s.kv_items.push_back(it);
         icost.push_back(it.it_end - it.it_begin);
       }
@@ -282,6 +283,78 @@ Schedule& get_schedule(dta_tree* tree, int bm, int bn, int hkv, int group) {
     sorted.reserve(order.size());
     for (size_t i : order) sorted.push_back(s.kv_items[i]);
     s.kv_items.swap(sorted);
+  }
+  return s;
+}
+
+Schedule& get_segment_schedule(dta_tree* tree, int bm, int bn, int hkv, int group,
+                               int64_t t_begin, int64_t t_end) {
+  const std::array<uint64_t, 3> key = {
+      ((uint64_t)bm << 48) | ((uint64_t)bn << 32) | ((uint64_t)hkv << 16) | (uint64_t)group,
+      (uint64_t)t_begin, (uint64_t)t_end};
+  auto it = tree->segment_schedules.find(key);
+  if (it != tree->segment_schedules.end()) return it->second;
+  Schedule& s = tree->segment_schedules[key];
+  s.bm = bm;
+  s.bn = bn;
+  s.hkv = hkv;
+  s.group = group;
+
+  // The keys the rows see: the segments of the ancestors (root first), then the
+  // node's own tokens before t_begin; every row sees all of them.  Adjacent
+  // pieces are merged.
+  const int32_t u0 = tree->token_node[(size_t)t_begin];
+  std::vector<int32_t> path;
+  for (int32_t a = tree->parent[u0]; a >= 0; a = tree->parent[a]) path.push_back(a);
+  std::vector<KeySeg> prefix;
+  auto add = [&](int64_t start, int64_t end) {
+    if (start >= end) return;
+    if (!prefix.empty() && prefix.back().end == start) prefix.back().end = (int32_t)end;
+    else prefix.push_back(KeySeg{(int32_t)start, (int32_t)end, 1, 0});
+  };
+  for (auto a = path.rbegin(); a != path.rend(); ++a) {
+    const int64_t off = tree->node_offset[*a];
+    add(off, off + tree->seg_len[*a]);
+  }
+  add(tree->node_offset[u0], t_begin);
+  int64_t prefix_keys = 0;
+  for (const KeySeg& ks : prefix) prefix_keys += ks.end - ks.start;
+
+  // ---- query tiles over the rows; a tile also sees the rows before it
+  for (int64_t t0 = t_begin; t0 < t_end; t0 += bm) {
+    const int64_t t1 = std::min<int64_t>(t_end, t0 + bm);
+    QTile qt;
+    qt.t0 = (int32_t)t0;
+    qt.t1 = (int32_t)t1;
+    qt.seg_begin = (int32_t)s.segs.size();
+    for (const KeySeg& ks : prefix) s.segs.push_back(ks);
+    if (t0 > t_begin) {
+      if (!prefix.empty() && s.segs.back().end == t_begin) s.segs.back().end = (int32_t)t0;
+      else s.segs.push_back(KeySeg{(int32_t)t_begin, (int32_t)t0, 1, 0});
+    }
+    qt.seg_end = (int32_t)s.segs.size();
+    s.q_tiles.push_back(qt);
+    s.fwd_tile_pairs += (prefix_keys + (t1 - t_begin)) * bm;
+  }
+  std::reverse(s.q_tiles.begin(), s.q_tiles.end());   // the last tile sees the most keys
+
+  // ---- key tiles: the prefix pieces (walk = all rows, no mask beyond padding),
+  // then the rows themselves (causal)
+  auto add_tiles = [&](int64_t start, int64_t end, bool own) {
+    for (int64_t k0 = start; k0 < end; k0 += bn) {
+      const int64_t k1 = std::min<int64_t>(end, k0 + bn);
+      const int64_t qb = own ? k0 : t_begin;
+      s.kv_tiles.push_back(KvTile{(int32_t)k0, (int32_t)k1, (int32_t)t_end, (int32_t)t_end,
+                                  (int32_t)qb, {0, 0, 0}});
+      s.bwd_tile_pairs += (t_end - qb) * bn;
+    }
+  };
+  add_tiles(t_begin, t_end, true);
+  for (const KeySeg& ks : prefix) add_tiles(ks.start, ks.end, false);
+  constexpr int kChunkRows = 64;
+  for (const KvTile& t : s.kv_tiles) {
+    const int64_t iters = (int64_t)((t.q_end - t.q_begin + kChunkRows - 1) / kChunkRows) * group;
+    s.kv_items.push_back(KvItem{t.k0, t.k1, t.q_end, t.q_full_end, 0, (int32_t)iters, -1, t.q_begin});
   }
   return s;
 }
