@@ -91,6 +91,60 @@ class Runner:
                           self.dq, self.dk, self.dv, self.ws)
         return tree
 
+    def push_pop_order(self):
+        """Calls of the paper's vanilla push / pop traversal (section 3.1): one
+        forward per node when it is pushed, one backward when it is popped.
+        [('F'|'B', t_begin, t_end)] in packed token coordinates."""
+        tree = self.dta.tree_build(self.parent, self.seg)
+        lay = tree.layout()
+        tree.destroy()
+        off = lay["node_offset"]
+        kids = [[] for _ in self.parent]
+        roots = []
+        for u, p in enumerate(self.parent):
+            (roots if p < 0 else kids[int(p)]).append(u)
+        calls, stack = [], [(r, False) for r in reversed(roots)]
+        while stack:
+            u, done = stack.pop()
+            rng = (int(off[u]), int(off[u]) + int(self.seg[u]))
+            if done:
+                calls.append(("B",) + rng)
+                continue
+            calls.append(("F",) + rng)
+            stack.append((u, True))
+            stack.extend((c, False) for c in reversed(kids[u]))
+        return calls
+
+    def step_segments(self, calls):
+        """The same work as step(), issued segment by segment in push / pop order."""
+        dta = self.dta
+        tree = dta.tree_build(self.parent, self.seg)
+        self.dk_acc.zero_()
+        self.dv_acc.zero_()
+        for tag, t0, t1 in calls:
+            if tag == "F":
+                dta.tree_attn_fwd_segment(tree, self.params, t0, t1, self.q, self.k, self.v, self.o, self.lse)
+            else:
+                dta.tree_attn_bwd_segment(tree, self.params, t0, t1, self.q, self.k, self.v, self.o,
+                                          self.lse, self.do, self.dq, self.dk_acc, self.dv_acc, self.ws)
+        return tree
+
+    def time_segment_steps(self, steps, warmup):
+        torch = self.torch
+        self.dk_acc = torch.empty(self.k.shape, dtype=torch.float32, device="cuda")
+        self.dv_acc = torch.empty_like(self.dk_acc)
+        calls = self.push_pop_order()
+        for _ in range(warmup):
+            self.step_segments(calls).destroy()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            self.step_segments(calls).destroy()
+        torch.cuda.synchronize()
+        sec = (time.perf_counter() - t0) / steps
+        del self.dk_acc, self.dv_acc
+        return sec, len(calls)
+
     def time_steps(self, steps, warmup):
         torch = self.torch
         for _ in range(warmup):
@@ -250,6 +304,7 @@ def main():
         r = Runner(parent, seg, heads, meta["tensor_seed"])
         sec = r.time_steps(steps, warmup)
         kern, info, sched = r.time_kernels(max(3, min(10, steps)))
+        seg_sec, seg_calls = r.time_segment_steps(max(1, min(5, steps)), 1)
         Hq, d = heads["n_q_heads"], heads["head_dim"]
         pairs = info["unique_pairs"]
         useful = pairs * Hq * 14 * d
@@ -268,6 +323,11 @@ def main():
             "C_full": info["rollout_tokens_full"] / info["n_tokens"],
             "C_attn_leaf": info["dense_pairs"] / pairs,
             "rollout_tokens_per_s_tree": info["rollout_tokens"] / sec,
+            # the same fwd+bwd issued one segment at a time in the paper's push / pop
+            # order (2 calls per node, dK/dV accumulated in fp32 across calls)
+            "segment_mode": {"ms_per_step": seg_sec * 1e3, "calls": seg_calls,
+                             "useful_tflops": useful / seg_sec / 1e12,
+                             "slowdown_vs_one_launch": seg_sec / sec},
         }
         del r
         torch.cuda.empty_cache()

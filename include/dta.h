@@ -18,7 +18,7 @@
  *  - attention calls only enqueue work on the given HIP stream and do not
  *    synchronise it.  The first attention call on a tree (or an explicit
  *    dta_tree_attn_prepare) allocates and uploads the tree's device metadata
- *    (stream-ordered allocation and copy on a stream the library owns; the call
+ *    (into a block of the library's own pool, by a copy on a stream the library owns; the call
  *    waits for that copy only, never for the caller's streams); later calls
  *    allocate nothing;
  *  - tensors are dense row-major [T, H, head_dim] with T = unique tree tokens in

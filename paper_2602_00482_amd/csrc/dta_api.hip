@@ -5,6 +5,7 @@
 #include <cstdio>
 #include <cstring>
 #include <initializer_list>
+#include <memory>
 #include <mutex>
 #include <vector>
 #include <new>
@@ -36,34 +37,90 @@ size_t bwd_workspace_bytes(dta_tree* tree, const dta::TileChoice& tc, const dta_
   return bytes;
 }
 
-// Device metadata lives in stream-ordered allocations made and filled on a
-// stream of the library's own (non-blocking, default priority, one per device,
-// kept until the process ends), so that preparing the next tree neither waits
-// for kernels the caller still has in flight nor, on release, for the device
-// to go idle.
-// Releases go to a second such stream: they wait there for the caller's
-// kernels, and an upload queued behind that wait would wait as well.
+// Device metadata lives in blocks from a small pool of the library's own and is
+// filled on a stream of the library's own (non-blocking, default priority, one
+// per device, kept until the process ends), so that preparing the next tree
+// neither waits for kernels the caller still has in flight nor, on release, for
+// the device to go idle.  A released block carries the event recorded after
+// the last launch that reads it and is handed out again only once that event
+// has completed; blocks are power-of-two sized and are not returned to the
+// driver while the process lives (hipFree would wait for the device).
 constexpr int kMaxDevices = 64;
-enum { kUpload = 0, kRelease = 1 };
 std::mutex g_stream_mu;
-hipStream_t g_stream[kMaxDevices][2];
+hipStream_t g_stream[kMaxDevices];
 bool g_stream_ok[kMaxDevices];
 
-int internal_stream(int dev, int which, hipStream_t* out) {
+int upload_stream(int dev, hipStream_t* out) {
   if (dev < 0 || dev >= kMaxDevices) return DTA_ERR_UNSUPPORTED;
   std::lock_guard<std::mutex> lock(g_stream_mu);
   if (!g_stream_ok[dev]) {
-    for (int i = 0; i < 2; ++i)
-      if (hipStreamCreateWithFlags(&g_stream[dev][i], hipStreamNonBlocking) != hipSuccess) {
-        fprintf(stderr, "dta: cannot create the metadata streams\n");
-        (void)hipGetLastError();
-        if (i == 1) (void)hipStreamDestroy(g_stream[dev][0]);
-        return DTA_ERR_HIP;
-      }
+    if (hipStreamCreateWithFlags(&g_stream[dev], hipStreamNonBlocking) != hipSuccess) {
+      fprintf(stderr, "dta: cannot create the metadata upload stream\n");
+      (void)hipGetLastError();
+      return DTA_ERR_HIP;
+    }
     g_stream_ok[dev] = true;
   }
-  *out = g_stream[dev][which];
+  *out = g_stream[dev];
   return DTA_OK;
+}
+
+struct EventHolder {
+  hipEvent_t ev;
+  explicit EventHolder(hipEvent_t e) : ev(e) {}
+  ~EventHolder() { (void)hipEventDestroy(ev); }
+};
+
+struct Block {
+  void* ptr;
+  size_t cap;
+  std::shared_ptr<EventHolder> busy_until;   // null: free right away
+};
+std::mutex g_pool_mu;
+std::vector<Block> g_pool[kMaxDevices];
+
+size_t size_class(size_t bytes) {
+  size_t c = 4096;
+  while (c < bytes) c <<= 1;
+  return c;
+}
+
+// A block of at least `bytes` on the current device `dev` that no launch reads
+// any more; *cap receives its size.  Null on failure.
+void* pool_alloc(int dev, size_t bytes, size_t* cap) {
+  const size_t c = size_class(bytes);
+  *cap = c;
+  {
+    std::lock_guard<std::mutex> lock(g_pool_mu);
+    std::vector<Block>& pool = g_pool[dev];
+    for (size_t i = 0; i < pool.size(); ++i) {
+      if (pool[i].cap != c) continue;
+      if (pool[i].busy_until && hipEventQuery(pool[i].busy_until->ev) != hipSuccess) {
+        (void)hipGetLastError();   // not ready yet: not an error
+        continue;
+      }
+      void* p = pool[i].ptr;
+      pool[i] = pool.back();
+      pool.pop_back();
+      return p;
+    }
+  }
+  void* p = nullptr;
+  if (hipMalloc(&p, c) != hipSuccess) {
+    (void)hipGetLastError();
+    return nullptr;
+  }
+  return p;
+}
+
+void pool_release(int dev, void* ptr, size_t cap, std::shared_ptr<EventHolder> busy_until) {
+  if (!ptr) return;
+  if (dev < 0 || dev >= kMaxDevices) {
+    (void)hipFree(ptr);
+    return;
+  }
+  std::lock_guard<std::mutex> lock(g_pool_mu);
+  g_pool[dev].push_back(Block{ptr, cap, std::move(busy_until)});
 }
 
 struct Part {
@@ -72,9 +129,10 @@ struct Part {
   void** dst;
 };
 
-// One allocation holding every part (each 256-byte aligned), filled from the
-// host and complete on return.
-int upload_parts(hipStream_t st, std::initializer_list<Part> parts, void** blob) {
+// One block holding every part (each 256-byte aligned), filled from the host
+// and complete on return.
+int upload_parts(int dev, hipStream_t st, std::initializer_list<Part> parts, void** blob,
+                 size_t* cap) {
   size_t total = 0;
   for (const Part& p : parts) total += round_up(p.bytes ? p.bytes : 1, 256);
   std::vector<char> staging;
@@ -83,11 +141,8 @@ int upload_parts(hipStream_t st, std::initializer_list<Part> parts, void** blob)
   } catch (const std::bad_alloc&) {
     return DTA_ERR_ALLOC;
   }
-  if (hipMallocAsync(blob, total, st) != hipSuccess) {
-    *blob = nullptr;
-    (void)hipGetLastError();
-    return DTA_ERR_ALLOC;
-  }
+  *blob = pool_alloc(dev, total, cap);
+  if (!*blob) return DTA_ERR_ALLOC;
   size_t off = 0;
   for (const Part& p : parts) {
     if (p.bytes) memcpy(staging.data() + off, p.src, p.bytes);
@@ -99,26 +154,19 @@ int upload_parts(hipStream_t st, std::initializer_list<Part> parts, void** blob)
   if (e != hipSuccess) {
     fprintf(stderr, "dta: metadata upload: %s\n", hipGetErrorString(e));
     (void)hipGetLastError();
-    (void)hipFreeAsync(*blob, st);
+    pool_release(dev, *blob, *cap, nullptr);
     *blob = nullptr;
     return DTA_ERR_HIP;
   }
   return DTA_OK;
 }
 
-// Releases a blob once the launches recorded in the tree's last_use event are
-// done, without blocking the host.
-void release_blob(dta_tree* tree, void* blob, int dev) {
+// Used when a tree moves to another device: waits for the launches that still
+// read the old copies (rare path), then returns the block to its pool.
+void release_blob_blocking(dta_tree* tree, void* blob, size_t cap, int dev) {
   if (!blob) return;
-  int cur = -1;
-  hipStream_t st;
-  if (hipGetDevice(&cur) == hipSuccess && cur == dev &&
-      internal_stream(dev, kRelease, &st) == DTA_OK) {
-    if (tree->used) (void)hipStreamWaitEvent(st, (hipEvent_t)tree->last_use, 0);
-    if (hipFreeAsync(blob, st) == hipSuccess) return;
-  }
-  (void)hipGetLastError();
-  (void)hipFree(blob);   // other device current, or no stream: blocking release
+  if (tree->used) (void)hipEventSynchronize((hipEvent_t)tree->last_use);
+  pool_release(dev, blob, cap, nullptr);
 }
 
 template <typename T>
@@ -153,7 +201,7 @@ int ensure_device(dta_tree* tree, const dta::TileChoice& tc, const dta_attn_para
     return DTA_OK;
   }
   hipStream_t us;
-  if ((st = internal_stream(dev, kUpload, &us)) != DTA_OK) return st;
+  if ((st = upload_stream(dev, &us)) != DTA_OK) return st;
   if (!tree->last_use) {
     hipEvent_t ev;
     if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) {
@@ -163,24 +211,25 @@ int ensure_device(dta_tree* tree, const dta::TileChoice& tc, const dta_attn_para
     tree->last_use = ev;
   }
   if (tree->kend_device != dev) {
-    release_blob(tree, tree->d_token_kend, tree->kend_device);
+    release_blob_blocking(tree, tree->d_token_kend, tree->d_kend_cap, tree->kend_device);
     tree->d_token_kend = nullptr;
     tree->kend_device = -1;
     void* blob = nullptr;
-    if ((st = upload_parts(us, {part_of(tree->token_kend, &tree->d_token_kend)}, &blob)) != DTA_OK)
+    if ((st = upload_parts(dev, us, {part_of(tree->token_kend, &tree->d_token_kend)}, &blob,
+                           &tree->d_kend_cap)) != DTA_OK)
       return st;
     tree->kend_device = dev;
   }
   if (s->device != dev) {
-    release_blob(tree, s->d_blob, s->device);
+    release_blob_blocking(tree, s->d_blob, s->d_blob_cap, s->device);
     s->d_blob = nullptr;
     s->device = -1;
-    if ((st = upload_parts(us,
+    if ((st = upload_parts(dev, us,
                            {part_of(s->q_tiles, &s->d_q_tiles), part_of(s->segs, &s->d_segs),
                             part_of(s->kv_tiles, &s->d_kv_tiles),
                             part_of(s->kv_items, &s->d_kv_items),
                             part_of(s->kv_reduce, &s->d_kv_reduce)},
-                           &s->d_blob)) != DTA_OK)
+                           &s->d_blob, &s->d_blob_cap)) != DTA_OK)
       return st;
     s->device = dev;
   }
@@ -221,10 +270,18 @@ extern "C" {
 
 void dta_tree_destroy(dta_tree_t* tree) {
   if (!tree) return;
-  release_blob(tree, tree->d_token_kend, tree->kend_device);
-  for (auto& kv : tree->schedules) release_blob(tree, kv.second.d_blob, kv.second.device);
-  for (auto& kv : tree->segment_schedules) release_blob(tree, kv.second.d_blob, kv.second.device);
-  if (tree->last_use) (void)hipEventDestroy((hipEvent_t)tree->last_use);
+  // the device copies go back to the pool together with the event after the
+  // tree's last launch; the pool hands them out again once it has completed
+  std::shared_ptr<EventHolder> busy;
+  if (tree->last_use) {
+    busy = std::make_shared<EventHolder>((hipEvent_t)tree->last_use);
+    if (!tree->used) busy.reset();   // never recorded: destroys the event, blocks are free at once
+  }
+  pool_release(tree->kend_device, tree->d_token_kend, tree->d_kend_cap, busy);
+  for (auto& kv : tree->schedules)
+    pool_release(kv.second.device, kv.second.d_blob, kv.second.d_blob_cap, busy);
+  for (auto& kv : tree->segment_schedules)
+    pool_release(kv.second.device, kv.second.d_blob, kv.second.d_blob_cap, busy);
   delete tree;
 }
 

@@ -82,6 +82,7 @@ struct Schedule {
   // the typed pointers below point into
   int device = -1;
   void* d_blob = nullptr;
+  size_t d_blob_cap = 0;
   QTile* d_q_tiles = nullptr;
   KeySeg* d_segs = nullptr;
   KvTile* d_kv_tiles = nullptr;
@@ -105,6 +106,7 @@ struct dta_tree {
   // schedules of segment calls, keyed by (tile configuration, t_begin, t_end)
   std::map<std::array<uint64_t, 3>, dta::Schedule> segment_schedules;
   int32_t* d_token_kend = nullptr;
+  size_t d_kend_cap = 0;
   int kend_device = -1;
   void* last_use = nullptr;   // hipEvent_t recorded after every launch that reads the device copies
   bool used = false;          // last_use has been recorded at least once

@@ -149,3 +149,49 @@ def test_segment_argument_errors():
     dta.tree_attn_fwd_segment(tree, p, 40, 64, q, k, v, o, lse)              # a valid call still works
     torch.cuda.synchronize()
     tree.destroy()
+
+
+def test_back_to_back_trees_without_synchronisation():
+    """Several trees run one after another on the stream, each destroyed right
+    after its last call and none synchronised in between (the next tree's
+    metadata is uploaded while the previous tree's kernels are still queued):
+    every tree's results must equal those of the same tree run alone."""
+    rng = np.random.default_rng(77)
+    Hq, Hkv, d = 8, 2, 128
+    scale = 1.0 / math.sqrt(d)
+    p = dta.AttnParams(Hq, Hkv, d, float(scale), dta.BF16)
+    jobs = []
+    for i in range(4):
+        parent, seg = random_tree(rng, 10 + i, 260)
+        T = int(np.sum(seg))
+        inp = make_inputs_numpy(T, Hq, Hkv, d, 50 + i, dtype="bf16")
+        t = {n: torch.from_numpy(a).cuda().to(torch.bfloat16).contiguous() for n, a in inp.items()}
+        trace = X.vanilla_dta(parent, seg, *(np.zeros((T, h, 2)) for h in (Hq, Hkv, Hkv, Hq)), scale)["trace"]
+        jobs.append((parent, seg, T, t, trace))
+
+    def run(job, sync):
+        parent, seg, T, t, trace = job
+        tree = dta.tree_build(parent, seg)
+        o = torch.zeros_like(t["q"])
+        lse = torch.zeros((T, Hq), dtype=torch.float32, device="cuda")
+        dq = torch.zeros_like(t["q"])
+        dk = torch.zeros((T, Hkv, d), dtype=torch.float32, device="cuda")
+        dv = torch.zeros_like(dk)
+        ws = torch.empty(max(256, dta.workspace_bytes(tree, p, True)), dtype=torch.uint8, device="cuda")
+        for tag, node, t0, t1 in trace:
+            if tag == "FWD":
+                dta.tree_attn_fwd_segment(tree, p, t0, t1, t["q"], t["k"], t["v"], o, lse)
+            else:
+                dta.tree_attn_bwd_segment(tree, p, t0, t1, t["q"], t["k"], t["v"], o, lse, t["do"], dq, dk, dv, ws)
+        if sync:
+            torch.cuda.synchronize()
+        tree.destroy()
+        return o, lse, dq, dk, dv
+
+    alone = [run(j, True) for j in jobs]
+    for rep in range(3):
+        together = [run(j, False) for j in jobs]
+        torch.cuda.synchronize()
+        for a, b in zip(alone, together):
+            for x, y in zip(a, b):
+                assert torch.equal(x, y)
