@@ -67,6 +67,7 @@ int upload_stream(int dev, hipStream_t* out) {
 
 struct EventHolder {
   hipEvent_t ev;
+  bool done = false;   // the event has been seen complete (guarded by g_pool_mu)
   explicit EventHolder(hipEvent_t e) : ev(e) {}
   ~EventHolder() { (void)hipEventDestroy(ev); }
 };
@@ -77,7 +78,9 @@ struct Block {
   std::shared_ptr<EventHolder> busy_until;   // null: free right away
 };
 std::mutex g_pool_mu;
-std::vector<Block> g_pool[kMaxDevices];
+// never destroyed: at process exit the HIP runtime may already be gone when
+// static destructors run, and the blocks' events must not be touched then
+std::vector<Block>* const g_pool = new std::vector<Block>[kMaxDevices];
 
 size_t size_class(size_t bytes) {
   size_t c = 4096;
@@ -93,11 +96,18 @@ void* pool_alloc(int dev, size_t bytes, size_t* cap) {
   {
     std::lock_guard<std::mutex> lock(g_pool_mu);
     std::vector<Block>& pool = g_pool[dev];
+    const EventHolder* not_ready = nullptr;   // all blocks of one tree share a holder: ask once
     for (size_t i = 0; i < pool.size(); ++i) {
       if (pool[i].cap != c) continue;
-      if (pool[i].busy_until && hipEventQuery(pool[i].busy_until->ev) != hipSuccess) {
-        (void)hipGetLastError();   // not ready yet: not an error
-        continue;
+      EventHolder* h = pool[i].busy_until.get();
+      if (h && !h->done) {
+        if (h == not_ready) continue;
+        if (hipEventQuery(h->ev) != hipSuccess) {
+          (void)hipGetLastError();   // not ready yet: not an error
+          not_ready = h;
+          continue;
+        }
+        h->done = true;
       }
       void* p = pool[i].ptr;
       pool[i] = pool.back();

@@ -508,3 +508,97 @@ def test_chunked_pops_change_nothing_and_run_last_chunk_first():
         for node, chunks in per_node.items():
             assert all(a[0] == b[1] for a, b in zip(chunks, chunks[1:]))     # right to left, contiguous
             assert max(t1 - t0 for t0, t1 in chunks) <= block
+
+
+# --------------------------- rollouts -> prefix tree, partitioning (oracle D)
+import itertools
+
+from oracle import rollout_tree as R
+
+
+def _random_rollouts(rng, n, alphabet, max_len, p_extend=0.5):
+    """Sequences that share prefixes: each new one copies a random prefix of an
+    earlier one (sometimes all of it: containment / duplicates) and appends."""
+    seqs = [list(rng.integers(0, alphabet, size=int(rng.integers(1, max_len + 1))))]
+    for _ in range(n - 1):
+        src = seqs[int(rng.integers(0, len(seqs)))]
+        keep = int(rng.integers(0, len(src) + 1))
+        extra = int(rng.integers(0 if keep else 1, max_len + 1)) if rng.random() < p_extend or keep == 0 else 0
+        s = list(src[:keep]) + list(rng.integers(0, alphabet, size=extra))
+        seqs.append(s if s else [int(rng.integers(0, alphabet))])
+    return [[int(t) for t in s] for s in seqs]
+
+
+def _paths(tree):
+    """Token sequence of the root-to-node path of every node."""
+    off = np.concatenate([[0], np.cumsum(tree["seg_len"])])
+    out = []
+    for u, p in enumerate(tree["parent"]):
+        own = tree["tokens"][off[u]:off[u + 1]]
+        out.append((out[p] if p >= 0 else []) + list(own))
+    return out
+
+
+def test_prefix_tree_round_trip_and_structure():
+    rng = np.random.default_rng(91)
+    for trial in range(60):
+        seqs = _random_rollouts(rng, int(rng.integers(1, 12)), int(rng.integers(1, 4)), 7)
+        tree = R.build_tree(seqs)
+        paths = _paths(tree)
+        for s, u in zip(seqs, tree["seq_node"]):
+            assert paths[u] == s                                   # every rollout is a root-to-node path
+        parent, seg_len = tree["parent"], tree["seg_len"]
+        kids = [[] for _ in parent]
+        for u, p in enumerate(parent):
+            assert p < u                                           # preorder numbering
+            if p >= 0:
+                kids[p].append(u)
+        ends = set(tree["seq_node"])
+        off = np.concatenate([[0], np.cumsum(seg_len)])
+        for u in range(len(parent)):
+            assert seg_len[u] >= 1
+            assert len(kids[u]) != 1 or u in ends                  # maximal merging: no pointless unary node
+            assert len(kids[u]) > 0 or u in ends                   # every leaf ends a rollout
+            firsts = [tree["tokens"][off[c]] for c in kids[u]]
+            assert firsts == sorted(set(firsts))                   # children: distinct first tokens, ascending
+        roots = [tree["tokens"][off[u]] for u, p in enumerate(parent) if p < 0]
+        assert roots == sorted(set(roots))
+        # packed order is the library's DFS preorder (children in ascending id): identity layout
+        assert L.preorder(parent) == list(range(len(parent)))
+        # tree tokens = appendix formula |pi_1| + sum(|pi_i| - LCP(pi_{i-1}, pi_i)) over the lexicographic order
+        pi = [seqs[i] for i in tree["order"]]
+        assert pi == sorted(pi)
+        T = len(pi[0]) + sum(len(pi[i]) - R.lcp(pi[i - 1], pi[i]) for i in range(1, len(pi)))
+        assert T == len(tree["tokens"]) == sum(seg_len)
+
+
+def test_prefix_tree_worked_example():
+    """Hand-checked: 'abc', 'abd', 'ab', 'x', 'abd' -> a b | c, d ; x."""
+    seqs = [[1, 2, 3], [1, 2, 4], [1, 2], [9], [1, 2, 4]]
+    t = R.build_tree(seqs)
+    assert t["parent"] == [-1, 0, 0, -1] and t["seg_len"] == [2, 1, 1, 1]
+    assert t["tokens"] == [1, 2, 3, 4, 9] and t["seq_node"] == [1, 2, 0, 3, 2]
+    assert t["order"] == [2, 0, 1, 4, 3]
+    assert R.lcp([1, 2, 3], [1, 2, 4]) == 2 and R.lcp([1], [1, 2]) == 1 and R.lcp([], [1]) == 0
+
+
+def test_partition_is_optimal_contiguous_and_within_the_duplication_bound():
+    rng = np.random.default_rng(92)
+    for trial in range(80):
+        seqs = _random_rollouts(rng, int(rng.integers(1, 9)), 3, 6)
+        N = len(seqs)
+        pi = sorted(seqs)
+        T = R.group_cost(pi, 0, N - 1)
+        for K in range(1, N + 1):
+            order, cuts = R.partition(seqs, K)
+            assert [seqs[i] for i in order] == pi
+            assert len(cuts) == K and cuts[0][0] == 0 and cuts[-1][1] == N - 1
+            assert all(a <= b for a, b in cuts) and all(c[1] + 1 == d[0] for c, d in zip(cuts, cuts[1:]))
+            costs = [R.group_cost(pi, a, b) for a, b in cuts]
+            # brute force: best achievable largest group cost over ALL splits into at most K contiguous groups
+            best = min(max(R.group_cost(pi, a, b) for a, b in
+                           zip((0,) + tuple(c + 1 for c in cs), cs + (N - 1,)))
+                       for k in range(1, K + 1) for cs in itertools.combinations(range(N - 1), k - 1))
+            assert max(costs) == best
+            # section 4: at most (K-1) * longest sequence tokens beyond the single tree
+            assert T <= sum(costs) <= T + (K - 1) * max(len(s) for s in seqs)
