@@ -237,6 +237,61 @@ int dta_tree_attn_bwd_segment(dta_tree_t* tree, const dta_attn_params_t* params,
                               float* dk_acc, float* dv_acc, void* workspace,
                               size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Rollout sequences -> prefix tree, and load-balanced partitioning.  Host only,
+ * integer only.
+ *
+ * dta_rollouts_build merges N token sequences into the prefix tree of the
+ * paper's problem formulation (section 3): nodes are token segments, every
+ * sequence is a root-to-node path, and a node ends exactly where sequences
+ * branch or where one ends (a sequence contained in a longer one ends at an
+ * interior node; equal sequences share their node).  Nodes are numbered in DFS
+ * preorder with children in ascending order of their first token, i.e. in the
+ * lexicographic order of the sequences, which is a valid DFS order of the tree
+ * (section 4), so (parent, seg_len) passed to dta_tree_build are packed in
+ * exactly this order and `tokens` is the packed token-id array.
+ *   tokens      : host, concatenated token ids of all sequences.
+ *   seq_offsets : host, [n_seqs + 1], seq_offsets[0] = 0, strictly increasing
+ *                 (no empty sequence), else DTA_ERR_INVALID_ARG.
+ *   out         : receives a new object; free it with dta_rollouts_destroy.
+ * DTA_ERR_BAD_TREE if the tree would have more than 2^31 - 1 tokens.
+ */
+typedef struct dta_rollouts dta_rollouts_t;
+typedef struct {
+  int32_t n_seqs;
+  int32_t n_nodes;
+  int64_t n_tokens;         /* unique tree tokens                                              */
+  const int32_t* parent;    /* [n_nodes]  tree arrays for dta_tree_build                       */
+  const int32_t* seg_len;   /* [n_nodes]                                                       */
+  const int32_t* tokens;    /* [n_tokens] token ids in the packed order                        */
+  const int32_t* seq_node;  /* [n_seqs]   node at which input sequence i ends                  */
+  const int32_t* order;     /* [n_seqs]   input index of the i-th sequence in lexicographic
+                                          order (a proper prefix first, ties in input order)   */
+  const int64_t* lcp;       /* [n_seqs]   common prefix length of the i-th and (i-1)-th
+                                          sequence of that order; lcp[0] = 0                   */
+} dta_rollouts_view_t;
+int dta_rollouts_build(const int32_t* tokens, const int64_t* seq_offsets, int32_t n_seqs,
+                       dta_rollouts_t** out);
+/* Borrowed host pointers into the object, valid until dta_rollouts_destroy. */
+int dta_rollouts_view(const dta_rollouts_t* rollouts, dta_rollouts_view_t* out);
+void dta_rollouts_destroy(dta_rollouts_t* rollouts);
+
+/*
+ * dta_rollouts_partition - the paper's load-balanced DFS-contiguous partitioning
+ * (section 4; pseudocode appendix): the sequences in lexicographic order are cut
+ * into k contiguous groups such that the largest group cost is minimal, the cost
+ * of a group being the tree tokens it needs (its first sequence, plus for every
+ * further one its length minus the common prefix with its predecessor).  Binary
+ * search on the cost bound with a greedy feasibility scan; if that yields fewer
+ * than k groups, the first group with more than one sequence is split after its
+ * first sequence until there are k.  1 <= k <= n_seqs, else DTA_ERR_INVALID_ARG.
+ *   group_begin : host out, [k + 1]; group g is positions
+ *                 [group_begin[g], group_begin[g+1]) of the lexicographic order.
+ *   group_cost  : host out, [k], tree tokens of each group.
+ */
+int dta_rollouts_partition(const dta_rollouts_t* rollouts, int32_t k, int32_t* group_begin,
+                           int64_t* group_cost);
+
 /* Static, human-readable name of a status code. */
 const char* dta_status_string(int status);
 

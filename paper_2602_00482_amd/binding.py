@@ -20,7 +20,8 @@ exported_symbols = [
     "dta_tree_build", "dta_tree_info", "dta_tree_layout", "dta_tree_schedule_info",
     "dta_tree_destroy", "dta_tree_attn_workspace_bytes", "dta_tree_attn_prepare",
     "dta_tree_attn_fwd", "dta_tree_attn_bwd", "dta_tree_attn_bwd_stages",
-    "dta_tree_attn_fwd_segment", "dta_tree_attn_bwd_segment", "dta_status_string",
+    "dta_tree_attn_fwd_segment", "dta_tree_attn_bwd_segment", "dta_rollouts_build",
+    "dta_rollouts_view", "dta_rollouts_destroy", "dta_rollouts_partition", "dta_status_string",
 ]
 
 
@@ -53,6 +54,13 @@ class _ScheduleInfo(C.Structure):
 class AttnParams(C.Structure):
     _fields_ = [("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("softmax_scale", C.c_float), ("dtype", C.c_int32)]
+
+
+class _RolloutsView(C.Structure):
+    _fields_ = [("n_seqs", C.c_int32), ("n_nodes", C.c_int32), ("n_tokens", C.c_int64),
+                ("parent", C.POINTER(C.c_int32)), ("seg_len", C.POINTER(C.c_int32)),
+                ("tokens", C.POINTER(C.c_int32)), ("seq_node", C.POINTER(C.c_int32)),
+                ("order", C.POINTER(C.c_int32)), ("lcp", C.POINTER(C.c_int64))]
 
 
 def load_library():
@@ -91,6 +99,14 @@ def load_library():
     lib.dta_tree_attn_bwd_segment.argtypes = ([vp, C.POINTER(AttnParams), C.c_int64, C.c_int64] + [vp] * 9 +
                                               [vp, C.c_size_t, vp])
     lib.dta_tree_attn_bwd_segment.restype = C.c_int
+    lib.dta_rollouts_build.argtypes = [i32p, C.POINTER(C.c_int64), C.c_int32, C.POINTER(vp)]
+    lib.dta_rollouts_build.restype = C.c_int
+    lib.dta_rollouts_view.argtypes = [vp, C.POINTER(_RolloutsView)]
+    lib.dta_rollouts_view.restype = C.c_int
+    lib.dta_rollouts_destroy.argtypes = [vp]
+    lib.dta_rollouts_destroy.restype = None
+    lib.dta_rollouts_partition.argtypes = [vp, C.c_int32, i32p, C.POINTER(C.c_int64)]
+    lib.dta_rollouts_partition.restype = C.c_int
     lib.dta_status_string.argtypes = [C.c_int]
     lib.dta_status_string.restype = C.c_char_p
     _lib = lib
@@ -284,3 +300,48 @@ def tree_attn_bwd_segment(tree: Tree, params: AttnParams, t_begin: int, t_end: i
                                                   _ptr(dq), _ptr(dk_acc), _ptr(dv_acc), _ptr(workspace),
                                                   ws_bytes, _stream())
     _check(st, "dta_tree_attn_bwd_segment")
+
+
+class Rollouts:
+    """Owns a dta_rollouts_t*: the prefix tree of a set of token sequences."""
+
+    def __init__(self, seqs):
+        seqs = [np.ascontiguousarray(s, dtype=np.int32) for s in seqs]
+        offs = np.zeros(len(seqs) + 1, dtype=np.int64)
+        offs[1:] = np.cumsum([len(s) for s in seqs])
+        toks = np.concatenate(seqs) if seqs else np.zeros(0, dtype=np.int32)
+        toks = np.ascontiguousarray(toks, dtype=np.int32)
+        h = C.c_void_p()
+        st = load_library().dta_rollouts_build(toks.ctypes.data_as(C.POINTER(C.c_int32)),
+                                               offs.ctypes.data_as(C.POINTER(C.c_int64)), len(seqs),
+                                               C.byref(h))
+        _check(st, "dta_rollouts_build")
+        self._h = h
+
+    def view(self) -> dict:
+        out = _RolloutsView()
+        _check(load_library().dta_rollouts_view(self._h, C.byref(out)), "dta_rollouts_view")
+        arr = lambda p, k: np.ctypeslib.as_array(p, shape=(k,)).copy() if k else np.zeros(0, dtype=np.int64)
+        return dict(parent=arr(out.parent, out.n_nodes), seg_len=arr(out.seg_len, out.n_nodes),
+                    tokens=arr(out.tokens, out.n_tokens), seq_node=arr(out.seq_node, out.n_seqs),
+                    order=arr(out.order, out.n_seqs), lcp=arr(out.lcp, out.n_seqs))
+
+    def partition(self, k: int):
+        """(group_begin [k+1], group_cost [k]) of dta_rollouts_partition."""
+        gb = np.zeros(max(k, 0) + 1, dtype=np.int32)
+        gc = np.zeros(max(k, 1), dtype=np.int64)
+        st = load_library().dta_rollouts_partition(self._h, int(k), gb.ctypes.data_as(C.POINTER(C.c_int32)),
+                                                   gc.ctypes.data_as(C.POINTER(C.c_int64)))
+        _check(st, "dta_rollouts_partition")
+        return gb, gc[:k]
+
+    def destroy(self):
+        if self._h:
+            load_library().dta_rollouts_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
