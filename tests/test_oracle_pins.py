@@ -602,3 +602,110 @@ def test_partition_is_optimal_contiguous_and_within_the_duplication_bound():
             assert max(costs) == best
             # section 4: at most (K-1) * longest sequence tokens beyond the single tree
             assert T <= sum(costs) <= T + (K - 1) * max(len(s) for s in seqs)
+
+
+# ------------------------- backward DFS order and leaf-order schedule (oracle E)
+from oracle import dfs_schedule as S
+
+
+def _run_schedule(parent, seg, q, k, v, do, scale, ops):
+    """Executes the operation list with the one-segment primitives."""
+    T, Hq, d = q.shape
+    Hkv = k.shape[1]
+    G = Hq // Hkv
+    off, _ = L.node_offsets(parent, seg)
+    path_tok = lambda leaf: np.concatenate([np.arange(off[u], off[u] + int(seg[u])) for u in L.node_path(parent, leaf)])
+    O = np.full((T, Hq, d), np.nan); LSE = np.full((T, Hq), np.nan)
+    dQ = np.full((T, Hq, d), np.nan); dK = np.zeros((T, Hkv, d)); dV = np.zeros((T, Hkv, d))
+    popped = np.zeros(T, dtype=int)
+    for tag, leaf, lo, hi in ops:
+        idx = path_tok(leaf)
+        own, ctx = idx[lo:hi], idx[:hi]
+        for h in range(Hq):
+            g = h // G
+            o, lse, p = X.fwd_segment(q[own, h], k[ctx, g], v[ctx, g], scale)
+            if tag != "BWD":
+                O[own, h], LSE[own, h] = o, lse
+            else:
+                assert np.array_equal(O[own, h], o)               # forwarded before it is popped
+                dq, dk, dv = X.bwd_segment(q[own, h], k[ctx, g], v[ctx, g], o, p, do[own, h], scale)
+                dQ[own, h] = dq
+                dK[ctx, g] += dk
+                dV[ctx, g] += dv
+        if tag == "BWD":
+            popped[own] += 1
+    assert (popped == 1).all()
+    return O, LSE, dQ, dK, dV
+
+
+def test_backward_dfs_order_and_schedule_worked_example():
+    """Root R (4 tokens) with children: leaf a (2), internal M (3) with leaves
+    b (5) and c (1), leaf e (6).  Depths: a 6, e 10, b 12, c 8.  At M the
+    children order is c (tail 8), b (tail 12), so tail(M) = 8; at R: leaves
+    first by tail: a (6), e (10), then M.  DFS leaf order a, e, c, b; pi is its
+    reverse b, c, e, a."""
+    parent = [-1, 0, 0, 2, 2, 0]
+    seg = [4, 2, 3, 5, 1, 6]       # ids: 0 R, 1 a, 2 M, 3 b, 4 c, 5 e
+    assert S.backward_dfs_order(parent, seg) == [3, 4, 5, 1]
+    ops, pi = S.schedule(parent, seg, block=0)
+    assert pi == [3, 4, 5, 1]
+    assert ops == [
+        ("FWD", 3, 0, 12), ("NOGRAD", 3, 0, 7),                 # next leaf c shares R+M = 7 tokens
+        ("REFWD", 3, 7, 12), ("BWD", 3, 7, 12),
+        ("FWD", 4, 7, 8),
+        ("REFWD", 4, 4, 8), ("BWD", 4, 4, 8),                   # c and M leave together: e shares only R
+        ("FWD", 5, 4, 10),
+        ("REFWD", 5, 4, 10), ("BWD", 5, 4, 10),
+        ("FWD", 1, 4, 6),
+        ("REFWD", 1, 0, 6), ("BWD", 1, 0, 6),
+    ]
+    ops4, _ = S.schedule(parent, seg, block=4)
+    # first leaf: 12 tokens to pop down to 7 -> p_pop = 5 >= 4: two chunks, anchor at 12 - 3 = 9
+    assert ops4[:6] == [("FWD", 3, 0, 12), ("NOGRAD", 3, 0, 9), ("REFWD", 3, 9, 12), ("BWD", 3, 9, 12),
+                        ("REFWD", 3, 7, 9), ("BWD", 3, 7, 9)]
+    assert S.path_ranges(parent, seg, 3, 2, 9) == [(2, 4), (6, 9), (9, 11)]   # packed: R 0-4, a 4-6, M 6-9, b 9-14
+
+
+@pytest.mark.parametrize("block", [0, 1, 5, 64])
+def test_schedule_discipline_counts_and_invariance(block):
+    rng = np.random.default_rng(300 + block)
+    for trial in range(6):
+        parent, seg = random_tree(rng, int(rng.integers(1, 14)), 9, n_roots=int(rng.integers(1, 3)))
+        ops, pi = S.schedule(parent, seg, block)
+        leaves = L.leaves(parent)
+        assert sorted(pi) == sorted(leaves)
+        # stack discipline in depth coordinates
+        depth, cur = 0, None
+        for tag, leaf, lo, hi in ops:
+            assert lo < hi
+            if tag == "FWD":
+                assert lo == depth and (cur is None or S.common_prefix_tokens(parent, seg, cur, leaf) >= lo)
+                depth, cur = hi, leaf
+            elif tag == "BWD":
+                assert hi == depth and leaf == cur and (block <= 0 or hi - lo <= block)
+                depth = lo
+            else:
+                assert leaf == cur and hi <= depth
+        assert depth == 0
+        # the paper's counts: one regular FWD per leaf, at most one FWD-NoGrad per leaf
+        assert sum(t[0] == "FWD" for t in ops) == len(leaves)
+        assert sum(t[0] == "NOGRAD" for t in ops) <= len(leaves)
+        assert [t for t in ops if t[0] == "REFWD"] == [("REFWD",) + t[1:] for t in ops if t[0] == "BWD"]
+        # invariance: same tensors as the rollout-expansion oracle
+        T = int(np.sum(seg))
+        q, k, v, do = _inputs(T, 4, 2, 6, seed=trial)
+        got = _run_schedule(parent, seg, q, k, v, do, 0.4, ops)
+        ref = A.forward(parent, seg, q, k, v, 0.4) + A.backward(parent, seg, q, k, v, do, 0.4)
+        for x, y in zip(got, ref):
+            assert np.abs(x - y).max() < 1e-11
+
+
+def test_leaf_first_order_needs_no_anchor_on_a_star():
+    """Siblings that are all leaves under one prompt (a GRPO group): every leaf
+    after the first shares exactly the prompt with its neighbours, so with an
+    infinite block no FWD-NoGrad is needed after the first leaf's."""
+    parent = [-1] + [0] * 6
+    seg = [10, 3, 7, 2, 9, 4, 5]
+    ops, pi = S.schedule(parent, seg, 0)
+    assert [seg[u] for u in pi] == sorted(seg[1:], reverse=True)       # reversed smaller-tail-first order
+    assert [t for t in ops if t[0] == "NOGRAD"] == [("NOGRAD", pi[0], 0, 10)]
