@@ -129,11 +129,19 @@ class Runner:
                                           self.lse, self.do, self.dq, self.dk_acc, self.dv_acc, self.ws)
         return tree
 
-    def time_segment_steps(self, steps, warmup):
+    def leaf_order_calls(self, block):
+        """Calls of the paper's optimised leaf-order schedule with pops chunked at
+        `block` tokens (dta_tree_plan); recomputing and anchor forwards included."""
+        tree = self.dta.tree_build(self.parent, self.seg)
+        plan = self.dta.tree_plan(tree, block)
+        tree.destroy()
+        return [("B" if op == self.dta.OP_BWD else "F", t0, t1) for op, _, t0, t1 in plan["calls"]]
+
+    def time_segment_steps(self, steps, warmup, calls=None):
         torch = self.torch
         self.dk_acc = torch.empty(self.k.shape, dtype=torch.float32, device="cuda")
         self.dv_acc = torch.empty_like(self.dk_acc)
-        calls = self.push_pop_order()
+        calls = self.push_pop_order() if calls is None else calls
         for _ in range(warmup):
             self.step_segments(calls).destroy()
         torch.cuda.synchronize()
@@ -305,6 +313,7 @@ def main():
         sec = r.time_steps(steps, warmup)
         kern, info, sched = r.time_kernels(max(3, min(10, steps)))
         seg_sec, seg_calls = r.time_segment_steps(max(1, min(5, steps)), 1)
+        lo_sec, lo_calls = r.time_segment_steps(max(1, min(5, steps)), 1, r.leaf_order_calls(2048))
         Hq, d = heads["n_q_heads"], heads["head_dim"]
         pairs = info["unique_pairs"]
         useful = pairs * Hq * 14 * d
@@ -327,7 +336,10 @@ def main():
             # order (2 calls per node, dK/dV accumulated in fp32 across calls)
             "segment_mode": {"ms_per_step": seg_sec * 1e3, "calls": seg_calls,
                              "useful_tflops": useful / seg_sec / 1e12,
-                             "slowdown_vs_one_launch": seg_sec / sec},
+                             "slowdown_vs_one_launch": seg_sec / sec,
+                             # the optimised leaf-order schedule, pops chunked at 2048 tokens
+                             "leaf_order_block2048": {"ms_per_step": lo_sec * 1e3, "calls": lo_calls,
+                                                      "slowdown_vs_one_launch": lo_sec / sec}},
         }
         del r
         torch.cuda.empty_cache()

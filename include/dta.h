@@ -292,6 +292,63 @@ void dta_rollouts_destroy(dta_rollouts_t* rollouts);
 int dta_rollouts_partition(const dta_rollouts_t* rollouts, int32_t k, int32_t* group_begin,
                            int64_t* group_cost);
 
+/*
+ * dta_tree_plan - the order in which the paper's optimised executor processes
+ * a tree, as a list of operations and of the segment calls that carry them out.
+ * Host only, integer only.
+ *
+ * Leaf order (pseudocode appendix, algorithm "Backward DFS Order"): bottom-up,
+ * a leaf's tail is its depth in tokens; an internal node orders its children
+ * leaf first, then by smaller tail (ties: smaller node id; the roots of a
+ * forest are ordered the same way) and takes its first child's tail; the leaf
+ * order of the DFS under these child orders, reversed, is leaf_order.
+ *
+ * Schedule (algorithm "Dynamic Tree Attention Backward", section 3.2): for each
+ * leaf in that order, pop what the active stack does not share with it, forward
+ * and push its suffix, and, where the next pop will leave part of the suffix on
+ * the stack, a FWD-NoGrad anchor for that part; at the end pop everything.  A
+ * pop of depths (lo, hi] is cut at evenly spaced boundaries at most `block`
+ * tokens apart (block <= 0: never cut) and runs last chunk first, each chunk as
+ * a recomputing forward followed by its backward.
+ *
+ * An operation works on depths [lo, hi) (0-based token positions) of the root
+ * path of `leaf`; for pops that is the leaf that was pushed last.  calls[
+ * call_ptr[i] .. call_ptr[i+1]) are operation i as rows [t_begin, t_end) of one
+ * node each, ready for dta_tree_attn_fwd_segment (DTA_OP_FWD, DTA_OP_REFWD,
+ * DTA_OP_FWD_NOGRAD) and dta_tree_attn_bwd_segment (DTA_OP_BWD); forwards list
+ * the root side first, backwards the leaf side first.  Issued in this order on
+ * zeroed accumulators the calls reproduce dta_tree_attn_fwd / _bwd.
+ */
+enum { DTA_OP_FWD = 0, DTA_OP_REFWD = 1, DTA_OP_BWD = 2, DTA_OP_FWD_NOGRAD = 3 };
+typedef struct {
+  int32_t op;      /* DTA_OP_*                                   */
+  int32_t leaf;    /* node id of the leaf whose root path is meant */
+  int64_t lo, hi;  /* depth range in tokens                       */
+} dta_plan_op_t;
+typedef struct {
+  int32_t op;      /* DTA_OP_* of the operation it belongs to     */
+  int32_t node;    /* node id                                     */
+  int64_t t_begin, t_end;  /* packed rows, inside that node       */
+} dta_plan_call_t;
+typedef struct dta_plan dta_plan_t;
+typedef struct {
+  int32_t n_leaves;
+  const int32_t* leaf_order;       /* [n_leaves] node ids                                  */
+  int64_t n_ops;
+  const dta_plan_op_t* ops;        /* [n_ops]                                              */
+  const int64_t* call_ptr;         /* [n_ops + 1]                                          */
+  int64_t n_calls;
+  const dta_plan_call_t* calls;    /* [n_calls]                                            */
+  int64_t n_fwd;                   /* regular forwards = n_leaves                          */
+  int64_t n_fwd_nograd;            /* anchors, at most n_leaves                            */
+  int64_t n_chunks;                /* popped chunks (one REFWD and one BWD each)           */
+  int64_t max_stack_tokens;        /* longest active stack = longest root-to-leaf path     */
+} dta_plan_view_t;
+int dta_tree_plan(const dta_tree_t* tree, int64_t block, dta_plan_t** out);
+/* Borrowed host pointers into the plan, valid until dta_plan_destroy. */
+int dta_plan_view(const dta_plan_t* plan, dta_plan_view_t* out);
+void dta_plan_destroy(dta_plan_t* plan);
+
 /* Static, human-readable name of a status code. */
 const char* dta_status_string(int status);
 

@@ -21,7 +21,8 @@ exported_symbols = [
     "dta_tree_destroy", "dta_tree_attn_workspace_bytes", "dta_tree_attn_prepare",
     "dta_tree_attn_fwd", "dta_tree_attn_bwd", "dta_tree_attn_bwd_stages",
     "dta_tree_attn_fwd_segment", "dta_tree_attn_bwd_segment", "dta_rollouts_build",
-    "dta_rollouts_view", "dta_rollouts_destroy", "dta_rollouts_partition", "dta_status_string",
+    "dta_rollouts_view", "dta_rollouts_destroy", "dta_rollouts_partition", "dta_tree_plan",
+    "dta_plan_view", "dta_plan_destroy", "dta_status_string",
 ]
 
 
@@ -54,6 +55,21 @@ class _ScheduleInfo(C.Structure):
 class AttnParams(C.Structure):
     _fields_ = [("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("softmax_scale", C.c_float), ("dtype", C.c_int32)]
+
+
+class _PlanOp(C.Structure):
+    _fields_ = [("op", C.c_int32), ("leaf", C.c_int32), ("lo", C.c_int64), ("hi", C.c_int64)]
+
+
+class _PlanCall(C.Structure):
+    _fields_ = [("op", C.c_int32), ("node", C.c_int32), ("t_begin", C.c_int64), ("t_end", C.c_int64)]
+
+
+class _PlanView(C.Structure):
+    _fields_ = [("n_leaves", C.c_int32), ("leaf_order", C.POINTER(C.c_int32)), ("n_ops", C.c_int64),
+                ("ops", C.POINTER(_PlanOp)), ("call_ptr", C.POINTER(C.c_int64)), ("n_calls", C.c_int64),
+                ("calls", C.POINTER(_PlanCall)), ("n_fwd", C.c_int64), ("n_fwd_nograd", C.c_int64),
+                ("n_chunks", C.c_int64), ("max_stack_tokens", C.c_int64)]
 
 
 class _RolloutsView(C.Structure):
@@ -107,6 +123,12 @@ def load_library():
     lib.dta_rollouts_destroy.restype = None
     lib.dta_rollouts_partition.argtypes = [vp, C.c_int32, i32p, C.POINTER(C.c_int64)]
     lib.dta_rollouts_partition.restype = C.c_int
+    lib.dta_tree_plan.argtypes = [vp, C.c_int64, C.POINTER(vp)]
+    lib.dta_tree_plan.restype = C.c_int
+    lib.dta_plan_view.argtypes = [vp, C.POINTER(_PlanView)]
+    lib.dta_plan_view.restype = C.c_int
+    lib.dta_plan_destroy.argtypes = [vp]
+    lib.dta_plan_destroy.restype = None
     lib.dta_status_string.argtypes = [C.c_int]
     lib.dta_status_string.restype = C.c_char_p
     _lib = lib
@@ -345,3 +367,27 @@ class Rollouts:
             self.destroy()
         except Exception:
             pass
+
+
+OP_FWD, OP_REFWD, OP_BWD, OP_FWD_NOGRAD = 0, 1, 2, 3
+
+
+def tree_plan(tree: Tree, block: int = 0) -> dict:
+    """dta_tree_plan as plain Python data: leaf_order, ops [(op, leaf, lo, hi)],
+    call_ptr, calls [(op, node, t_begin, t_end)] and the counters."""
+    lib = load_library()
+    h = C.c_void_p()
+    _check(lib.dta_tree_plan(tree.handle, int(block), C.byref(h)), "dta_tree_plan")
+    try:
+        v = _PlanView()
+        _check(lib.dta_plan_view(h, C.byref(v)), "dta_plan_view")
+        return dict(
+            leaf_order=[int(v.leaf_order[i]) for i in range(v.n_leaves)],
+            ops=[(v.ops[i].op, v.ops[i].leaf, int(v.ops[i].lo), int(v.ops[i].hi)) for i in range(v.n_ops)],
+            call_ptr=[int(v.call_ptr[i]) for i in range(v.n_ops + 1)],
+            calls=[(v.calls[i].op, v.calls[i].node, int(v.calls[i].t_begin), int(v.calls[i].t_end))
+                   for i in range(v.n_calls)],
+            n_fwd=int(v.n_fwd), n_fwd_nograd=int(v.n_fwd_nograd), n_chunks=int(v.n_chunks),
+            max_stack_tokens=int(v.max_stack_tokens))
+    finally:
+        lib.dta_plan_destroy(h)

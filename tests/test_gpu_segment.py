@@ -195,3 +195,41 @@ def test_back_to_back_trees_without_synchronisation():
         for a, b in zip(alone, together):
             for x, y in zip(a, b):
                 assert torch.equal(x, y)
+
+
+@pytest.mark.parametrize("dtype,d,block", [("f32", 64, 0), ("f32", 64, 50), ("bf16", 128, 0), ("bf16", 128, 200)])
+def test_leaf_order_plan_reproduces_the_whole_tree_results(dtype, d, block):
+    """The calls of dta_tree_plan (the paper's leaf-order schedule with chunked
+    pops), issued in order on zeroed accumulators, against the rollout-expansion
+    oracle."""
+    from oracle import dense_rollout as A
+    rng = np.random.default_rng(55 + block)
+    parent, seg = random_tree(rng, 14, 300 if dtype == "bf16" else 90, n_roots=2)
+    T, Hq, Hkv = int(np.sum(seg)), 8, 2
+    scale = 1.0 / math.sqrt(d)
+    inp = make_inputs_numpy(T, Hq, Hkv, d, 9, dtype=dtype)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    t = {n: torch.from_numpy(a).cuda().to(tdt).contiguous() for n, a in inp.items()}
+    tree = dta.tree_build(parent, seg)
+    p = dta.AttnParams(Hq, Hkv, d, float(scale), dta.F32 if dtype == "f32" else dta.BF16)
+    plan = dta.tree_plan(tree, block)
+    nan = float("nan")
+    o = torch.full_like(t["q"], nan)
+    lse = torch.full((T, Hq), nan, dtype=torch.float32, device="cuda")
+    dq = torch.full_like(t["q"], nan)
+    dk = torch.zeros((T, Hkv, d), dtype=torch.float32, device="cuda")
+    dv = torch.zeros_like(dk)
+    ws = torch.empty(max(256, dta.workspace_bytes(tree, p, True)), dtype=torch.uint8, device="cuda")
+    for op, node, t0, t1 in plan["calls"]:
+        if op == dta.OP_BWD:
+            dta.tree_attn_bwd_segment(tree, p, t0, t1, t["q"], t["k"], t["v"], o, lse, t["do"], dq, dk, dv, ws)
+        else:
+            dta.tree_attn_fwd_segment(tree, p, t0, t1, t["q"], t["k"], t["v"], o, lse)
+    torch.cuda.synchronize()
+    tree.destroy()
+    O, LSE = A.forward(parent, seg, inp["q"], inp["k"], inp["v"], scale)
+    dQ, dK, dV = A.backward(parent, seg, inp["q"], inp["k"], inp["v"], inp["do"], scale)
+    got = dict(o=o, lse=lse, dq=dq, dk=dk, dv=dv)
+    for name, ref in (("o", O), ("lse", LSE), ("dq", dQ), ("dk", dK), ("dv", dV)):
+        e = rel_err(got[name].double().cpu().numpy(), ref)
+        assert e <= TOL[dtype], (name, e)
