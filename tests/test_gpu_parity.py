@@ -57,7 +57,7 @@ def test_fp32_degenerate_trees():
     _compare(np.array([-1] * 5), np.array([3, 70, 1, 64, 65]), 2, 1, 64, "f32", seed=4)   # forest of single nodes
 
 
-@pytest.mark.parametrize("Hq,Hkv", [(4, 1), (8, 2), (2, 1), (1, 1), (3, 1), (16, 2)])
+@pytest.mark.parametrize("Hq,Hkv", [(4, 1), (8, 2), (2, 1), (1, 1), (3, 1), (16, 2), (32, 8), (16, 1), (5, 1)])
 def test_bf16_random_forests(Hq, Hkv):
     rng = np.random.default_rng(99 + Hq)
     for trial in range(3):
