@@ -265,6 +265,9 @@ def main():
     ap.add_argument("--others", type=str, default="3,4,5", help="configs reported as extra objects ('' = none)")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-segments", action="store_true",
+                    help="skip the segment-mode measurements (used for kernel-trace profiles, whose "
+                         "per-kernel averages should cover the one-launch path only)")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="no timing: two steps of --config, then a plain 1 GiB device copy; the program "
                          "to run under `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` (the copy "
@@ -306,14 +309,15 @@ def main():
         is_leaf[parent[parent >= 0]] = False
         return (lay["node_start_depth"] + seg)[is_leaf]
 
-    def measure(cfg, steps, warmup, with_dense, with_cpu):
+    def measure(cfg, steps, warmup, with_dense, with_cpu, with_segments=True):
         parent, seg, meta = config_tree(cfg)
         heads = config_heads(cfg)
         r = Runner(parent, seg, heads, meta["tensor_seed"])
         sec = r.time_steps(steps, warmup)
         kern, info, sched = r.time_kernels(max(3, min(10, steps)))
-        seg_sec, seg_calls = r.time_segment_steps(max(1, min(5, steps)), 1)
-        lo_sec, lo_calls = r.time_segment_steps(max(1, min(5, steps)), 1, r.leaf_order_calls(2048))
+        if with_segments:
+            seg_sec, seg_calls = r.time_segment_steps(max(1, min(5, steps)), 1)
+            lo_sec, lo_calls = r.time_segment_steps(max(1, min(5, steps)), 1, r.leaf_order_calls(2048))
         Hq, d = heads["n_q_heads"], heads["head_dim"]
         pairs = info["unique_pairs"]
         useful = pairs * Hq * 14 * d
@@ -332,15 +336,16 @@ def main():
             "C_full": info["rollout_tokens_full"] / info["n_tokens"],
             "C_attn_leaf": info["dense_pairs"] / pairs,
             "rollout_tokens_per_s_tree": info["rollout_tokens"] / sec,
+        }
+        if with_segments:
             # the same fwd+bwd issued one segment at a time in the paper's push / pop
             # order (2 calls per node, dK/dV accumulated in fp32 across calls)
-            "segment_mode": {"ms_per_step": seg_sec * 1e3, "calls": seg_calls,
-                             "useful_tflops": useful / seg_sec / 1e12,
-                             "slowdown_vs_one_launch": seg_sec / sec,
-                             # the optimised leaf-order schedule, pops chunked at 2048 tokens
-                             "leaf_order_block2048": {"ms_per_step": lo_sec * 1e3, "calls": lo_calls,
-                                                      "slowdown_vs_one_launch": lo_sec / sec}},
-        }
+            res["segment_mode"] = {"ms_per_step": seg_sec * 1e3, "calls": seg_calls,
+                                   "useful_tflops": useful / seg_sec / 1e12,
+                                   "slowdown_vs_one_launch": seg_sec / sec,
+                                   # the optimised leaf-order schedule, pops chunked at 2048 tokens
+                                   "leaf_order_block2048": {"ms_per_step": lo_sec * 1e3, "calls": lo_calls,
+                                                            "slowdown_vs_one_launch": lo_sec / sec}}
         del r
         torch.cuda.empty_cache()
         if with_dense:
@@ -354,7 +359,7 @@ def main():
         return res, kern, info, heads, cpu
 
     main_res, kern, info, heads, cpu = measure(args.config, args.steps, args.warmup,
-                                               not args.no_dense, not args.no_cpu)
+                                               not args.no_dense, not args.no_cpu, not args.no_segments)
     Hq, d = heads["n_q_heads"], heads["head_dim"]
     dom = max(KERNEL_FLOP_D, key=lambda k: kern[k])
     achieved = info["unique_pairs"] * Hq * KERNEL_FLOP_D[dom] * d / (kern[dom] * 1e-3) / 1e12
@@ -377,7 +382,7 @@ def main():
     for c in [int(x) for x in args.others.split(",") if x.strip()]:
         if c == args.config:
             continue
-        res, *_ = measure(c, max(2, min(5, args.steps)), 1, not args.no_dense, False)
+        res, *_ = measure(c, max(2, min(5, args.steps)), 1, not args.no_dense, False, not args.no_segments)
         others[WORKLOAD_NAMES[c]] = res
     if others:
         line["other_configs"] = others
