@@ -22,7 +22,11 @@
  *    waits for that copy only, never for the caller's streams); later calls
  *    allocate nothing;
  *  - tensors are dense row-major [T, H, head_dim] with T = unique tree tokens in
- *    the packed DFS order defined by dta_tree_build.
+ *    the packed DFS order defined by dta_tree_build;
+ *  - a tree may be used from several host threads (its lazily built schedules are
+ *    guarded); every attention call also records an event on its stream, which
+ *    is how dta_tree_destroy knows when the device copies are free, so a tree
+ *    must outlive any captured graph that replays calls made on it.
  */
 #ifndef DTA_H_
 #define DTA_H_
@@ -184,8 +188,9 @@ int dta_tree_attn_bwd(dta_tree_t* tree, const dta_attn_params_t* params, const v
  * dta_tree_attn_bwd_stages - the same backward pass, restricted to the stages in
  * stage_mask, for callers that need only some gradients or that time the
  * launches one by one.  dta_tree_attn_bwd equals DTA_BWD_ALL.  DTA_BWD_DQ and
- * DTA_BWD_DKDV read the D values DTA_BWD_DELTA leaves in the workspace, so the
- * delta stage must have run on the same workspace, o and d_o before them.
+ * DTA_BWD_DKDV read what DTA_BWD_DELTA leaves in the workspace (the D values
+ * and, in bf16 mode, lse rescaled for the kernels), so the delta stage must have
+ * run on the same workspace, o, lse, d_o and softmax_scale before them.
  * Outputs of stages that are not selected are not touched (and may be NULL).
  */
 enum { DTA_BWD_DELTA = 1, DTA_BWD_DQ = 2, DTA_BWD_DKDV = 4, DTA_BWD_ALL = 7 };
