@@ -142,3 +142,34 @@ def test_full_size_sampled_rows_and_invariants(cfg):
     ek, ev = _rel(got_dk, dK[rows_sub]), _rel(got_dv, dV[rows_sub])
     print(f"cfg{cfg} subtree of node {root}: {len(nodes)} nodes, {len(rows_sub)} keys: dk={ek:.2e} dv={ev:.2e}", flush=True)
     assert ek <= TOL and ev <= TOL
+
+
+@pytest.mark.parametrize("cfg,block", [(2, 0), (3, 2048)])
+def test_full_size_segment_calls_agree_with_the_one_launch_path(cfg, block):
+    """The paper's executor order at full size: the calls of dta_tree_plan issued
+    one by one on zeroed accumulators, against the one-launch results checked
+    above (both bf16 evaluations of the same sums)."""
+    parent, seg, (Hq, Hkv, d, scale), t = _run(cfg)
+    T = int(seg.sum())
+    p = dta.AttnParams(Hq, Hkv, d, scale, dta.BF16)
+    tree = dta.tree_build(parent, seg)
+    plan = dta.tree_plan(tree, block)
+    o = torch.zeros_like(t["q"])
+    lse = torch.zeros((T, Hq), dtype=torch.float32, device="cuda")
+    dq = torch.zeros_like(t["q"])
+    dk = torch.zeros((T, Hkv, d), dtype=torch.float32, device="cuda")
+    dv = torch.zeros_like(dk)
+    ws = torch.empty(max(256, dta.workspace_bytes(tree, p, True)), dtype=torch.uint8, device="cuda")
+    for op, node, t0, t1 in plan["calls"]:
+        if op == dta.OP_BWD:
+            dta.tree_attn_bwd_segment(tree, p, t0, t1, t["q"], t["k"], t["v"], o, lse, t["do"], dq, dk, dv, ws)
+        else:
+            dta.tree_attn_fwd_segment(tree, p, t0, t1, t["q"], t["k"], t["v"], o, lse)
+    torch.cuda.synchronize()
+    tree.destroy()
+    rel = lambda a, b: float((a.double() - b.double()).abs().max() / b.double().abs().max())
+    errs = dict(o=rel(o, t["o"]), lse=rel(lse, t["lse"]), dq=rel(dq, t["dq"]), dk=rel(dk, t["dk"]), dv=rel(dv, t["dv"]))
+    print(f"cfg{cfg} block {block}: {len(plan['calls'])} calls " + " ".join(f"{k}={v:.2e}" for k, v in errs.items()),
+          flush=True)
+    assert errs["lse"] <= 1e-5
+    assert all(e <= TOL for e in errs.values())
