@@ -354,6 +354,29 @@ int dta_tree_plan(const dta_tree_t* tree, int64_t block, dta_plan_t** out);
 int dta_plan_view(const dta_plan_t* plan, dta_plan_view_t* out);
 void dta_plan_destroy(dta_plan_t* plan);
 
+/*
+ * dta_probe_mfma_bf16 - measurement helper, not part of the method: enqueues a
+ * kernel that does nothing but bf16 matrix-core products (the instruction and
+ * block shape of the attention kernels, register operands, no memory traffic)
+ * so that a caller who times it gets the rate the matrix pipes of this GPU
+ * sustain under its power limit, the practical ceiling beside the published
+ * peak that the roofline of the attention kernels is priced against.
+ *
+ * n_blocks blocks of 256 threads, `iters` iterations of 16 products per wave.
+ * out   [n_blocks * 256] fp32, device: written (keeps the work observable).
+ * ticks [2 * n_blocks] uint64, device: per block, the shader-clock cycles and
+ *       the constant-rate wall-clock ticks the loop took; their ratio times
+ *       the wall-clock rate gives the shader clock during the run.
+ * *flop (host, may be NULL) receives the floating-point operations of the
+ * launch: n_blocks * 4 waves * iters * 16 * (2*32*32*16).
+ * *wall_clock_khz (host, may be NULL) receives the rate of the wall-clock
+ * counter on the current device.
+ * Asynchronous on hip_stream; allocates nothing.  INVALID_ARG for null buffers,
+ * n_blocks outside [1, 2^20] or iters outside [1, 2^24].
+ */
+int dta_probe_mfma_bf16(int32_t n_blocks, int32_t iters, float* out, uint64_t* ticks, void* hip_stream,
+                        int64_t* flop, int32_t* wall_clock_khz);
+
 /* Static, human-readable name of a status code. */
 const char* dta_status_string(int status);
 

@@ -10,7 +10,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libdta.so")
-SOURCES = ["dta_tree.cpp", "dta_rollouts.cpp", "dta_plan.cpp", "dta_api.hip", "dta_f32_kernels.hip", "dta_bf16_fwd.hip", "dta_bf16_bwd.hip"]
+SOURCES = ["dta_tree.cpp", "dta_rollouts.cpp", "dta_plan.cpp", "dta_api.hip", "dta_f32_kernels.hip", "dta_bf16_fwd.hip", "dta_bf16_bwd.hip", "dta_probe.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",

@@ -128,3 +128,25 @@ def test_destroy_right_after_launch_and_metadata_reuse():
     for a, b in zip(outs[0], outs[1]):
         for u, v in zip(a, b):
             assert torch.equal(u, v)
+
+
+def test_mfma_rate_probe_is_linear_in_its_iteration_count():
+    """The probe's operands are constant over the loop and exactly representable
+    (multiples of 1/64 below 2 in size), so every accumulator after n iterations is
+    n times its value after one, exactly, as long as the sums stay below 2^24/4096;
+    the operation count follows the documented formula; both counters advance."""
+    n_blocks = 3
+    outs = {}
+    for iters in (1, 2, 8):
+        out = torch.full((n_blocks * 256,), float("nan"), dtype=torch.float32, device="cuda")
+        ticks = torch.zeros(2 * n_blocks, dtype=torch.int64, device="cuda")
+        flop, khz = dta.probe_mfma_bf16(n_blocks, iters, out, ticks)
+        torch.cuda.synchronize()
+        assert flop == n_blocks * 4 * iters * 16 * 2 * 32 * 32 * 16
+        assert khz > 0
+        assert bool((ticks > 0).all())
+        assert bool(torch.isfinite(out).all())
+        outs[iters] = out.cpu()
+    assert float(outs[1].abs().max()) > 0
+    assert torch.equal(outs[2], 2 * outs[1])
+    assert torch.equal(outs[8], 8 * outs[1])

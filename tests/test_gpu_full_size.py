@@ -1,4 +1,4 @@
-"""GPU parity at the benchmark's full sizes (configurations 2-5, bf16), in the
+"""GPU parity at the benchmark's full sizes (configurations 2-7, bf16), in the
 launch configuration bench.py times.  The fp64 oracle cannot cover whole tensors
 here, so it is run on sampled outputs it can compute one by one:
 
@@ -64,7 +64,7 @@ def _subtree_nodes(parent, root):
     return out
 
 
-@pytest.mark.parametrize("cfg", [2, 3, 4, 5])
+@pytest.mark.parametrize("cfg", [2, 3, 4, 5, 6, 7])
 def test_full_size_sampled_rows_and_invariants(cfg):
     parent, seg, (Hq, Hkv, d, scale), t = _run(cfg)
     G = Hq // Hkv

@@ -18,7 +18,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "dta.h")).read()
-    declared = set(re.findall(r"\b(dta_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(dta_[a-z0-9_]+)\s*\(", header))
     assert declared == set(dta.exported_symbols)
     lib = dta.load_library()
     for name in declared:
@@ -153,6 +153,13 @@ def test_error_codes():
     assert lib.dta_tree_attn_bwd(tree.handle, C.byref(good), z, z, z, z, z, z, z, z, z, z, 0, z) == -1
     assert lib.dta_tree_attn_bwd_stages(tree.handle, C.byref(good), z, z, z, z, z, z, z, z, z, z, 0, z, 0) == -1
     assert lib.dta_tree_attn_bwd_stages(tree.handle, C.byref(good), z, z, z, z, z, z, z, z, z, z, 0, z, 8) == -1
+    # the rate probe checks its arguments before launching anything
+    one = C.c_void_p(1)
+    assert lib.dta_probe_mfma_bf16(1, 1, z, one, z, None, None) == -1
+    assert lib.dta_probe_mfma_bf16(1, 1, one, z, z, None, None) == -1
+    assert lib.dta_probe_mfma_bf16(0, 1, one, one, z, None, None) == -1
+    assert lib.dta_probe_mfma_bf16(1, 0, one, one, z, None, None) == -1
+    assert lib.dta_probe_mfma_bf16(2 ** 20 + 1, 1, one, one, z, None, None) == -1
     lib.dta_tree_destroy(None)
     tree.destroy()
 

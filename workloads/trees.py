@@ -5,7 +5,9 @@ root-to-leaf path is one rollout (paper section 3, problem formulation).  The
 five shapes below stand in for the paper's tau^2-bench / GRPO rollouts, which
 are not available: a shared prompt with sampled responses, a multi-turn agent
 forest with a shared system prompt, a deep long-context tree, and a large mixed
-forest.  All draws use numpy's PCG64 via default_rng(seed) so that every run,
+forest.  Three more (6..8) take the shape of the paper's low-compression
+settings (appendix, throughput under low compression rates): short shared
+prefixes, C between 1.4 and 1.01.  All draws use numpy's PCG64 via default_rng(seed) so that every run,
 on any machine, sees the same trees.
 """
 from __future__ import annotations
@@ -13,7 +15,8 @@ from __future__ import annotations
 import numpy as np
 
 # name -> (tree seed, tensor seed)
-CONFIGS = {1: (1001, 2001), 2: (1002, 2002), 3: (1003, 2003), 4: (1004, 2004), 5: (1005, 2005)}
+CONFIGS = {1: (1001, 2001), 2: (1002, 2002), 3: (1003, 2003), 4: (1004, 2004), 5: (1005, 2005),
+           6: (1006, 2006), 7: (1007, 2007), 8: (1008, 2008)}
 
 _HEADS = {
     1: dict(n_q_heads=4, n_kv_heads=4, head_dim=64, dtype="f32"),
@@ -21,11 +24,14 @@ _HEADS = {
     3: dict(n_q_heads=32, n_kv_heads=8, head_dim=128, dtype="bf16"),
     4: dict(n_q_heads=32, n_kv_heads=8, head_dim=128, dtype="bf16"),
     5: dict(n_q_heads=64, n_kv_heads=8, head_dim=128, dtype="bf16"),
+    6: dict(n_q_heads=32, n_kv_heads=8, head_dim=128, dtype="bf16"),
+    7: dict(n_q_heads=32, n_kv_heads=8, head_dim=128, dtype="bf16"),
+    8: dict(n_q_heads=32, n_kv_heads=8, head_dim=128, dtype="bf16"),
 }
 
 
 def config_heads(cfg: int) -> dict:
-    """Head counts, head_dim and dtype of benchmark configuration `cfg` (1..5)."""
+    """Head counts, head_dim and dtype of benchmark configuration `cfg` (1..8)."""
     return dict(_HEADS[cfg])
 
 
@@ -103,8 +109,39 @@ def _cfg5(rng, n_trees=64, cap=262144, min_len=16):
     return np.asarray(parent, dtype=np.int32), seg, scale
 
 
+def _prompt_groups(rng, n_prompts, n_resp, prompt_lo, prompt_hi, resp_lo, resp_hi):
+    """A forest of `n_prompts` trees: a prompt and `n_resp` sampled responses."""
+    parent, seg = [], []
+    for _ in range(n_prompts):
+        root = len(parent)
+        parent.append(-1)
+        seg.append(int(rng.integers(prompt_lo, prompt_hi + 1)))
+        for x in rng.integers(resp_lo, resp_hi + 1, size=n_resp):
+            parent.append(root)
+            seg.append(int(x))
+    return _as_arrays(parent, seg)
+
+
+def _cfg6(rng):
+    # agent rollouts with the global prompt removed: what is left to share is the
+    # first part of each dialogue (average rollout about 1.6K tokens, C about 1.4)
+    return _prompt_groups(rng, 64, 2, 700, 1100, 400, 1000)
+
+
+def _cfg7(rng):
+    # grade-school-maths style: a short question, 8 long sampled answers
+    # (average rollout about 1.8K tokens, C about 1.09)
+    return _prompt_groups(rng, 8, 8, 100, 240, 800, 2500)
+
+
+def _cfg8(rng):
+    # competition-maths style: one short problem, 16 answers of about 16K tokens
+    # (C about 1.008)
+    return _prompt_groups(rng, 1, 16, 130, 130, 12288, 20480)
+
+
 def config_tree(cfg: int):
-    """Return (parent, seg_len, info) for benchmark configuration `cfg` (1..5)."""
+    """Return (parent, seg_len, info) for benchmark configuration `cfg` (1..8)."""
     rng = np.random.default_rng(CONFIGS[cfg][0])
     info = {"cfg": cfg, "tree_seed": CONFIGS[cfg][0], "tensor_seed": CONFIGS[cfg][1]}
     if cfg == 1:
@@ -118,6 +155,12 @@ def config_tree(cfg: int):
     elif cfg == 5:
         p, s, scale = _cfg5(rng)
         info["length_scale"] = scale
+    elif cfg == 6:
+        p, s = _cfg6(rng)
+    elif cfg == 7:
+        p, s = _cfg7(rng)
+    elif cfg == 8:
+        p, s = _cfg8(rng)
     else:
         raise ValueError(f"unknown config {cfg}")
     return p, s, info
