@@ -181,8 +181,8 @@ class Runner:
              self.dq, self.dk, self.dv, self.ws)
         launches = {
             "fwd": lambda: dta.tree_attn_fwd(tree, self.params, self.q, self.k, self.v, self.o, self.lse),
-            "delta": lambda: dta.tree_attn_bwd(*a, stages=dta.BWD_DELTA),
-            "dq": lambda: dta.tree_attn_bwd(*a, stages=dta.BWD_DQ),
+            # as the step issues it: the dQ launch also computes the row statistics D = dO.O
+            "dq": lambda: dta.tree_attn_bwd(*a, stages=dta.BWD_DELTA | dta.BWD_DQ),
             "dkdv": lambda: dta.tree_attn_bwd(*a, stages=dta.BWD_DKDV),
         }
         out = {}

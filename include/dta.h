@@ -190,7 +190,10 @@ int dta_tree_attn_bwd(dta_tree_t* tree, const dta_attn_params_t* params, const v
  * launches one by one.  dta_tree_attn_bwd equals DTA_BWD_ALL.  DTA_BWD_DQ and
  * DTA_BWD_DKDV read what DTA_BWD_DELTA leaves in the workspace (the D values
  * and, in bf16 mode, lse rescaled for the kernels), so the delta stage must have
- * run on the same workspace, o, lse, d_o and softmax_scale before them.
+ * run on the same workspace, o, lse, d_o and softmax_scale before them.  In
+ * bf16 mode a call that asks for DTA_BWD_DELTA and DTA_BWD_DQ together computes
+ * D inside the dQ launch (no separate pass over o and d_o) and leaves the same
+ * values in the workspace; results do not depend on how the stages are grouped.
  * Outputs of stages that are not selected are not touched (and may be NULL).
  */
 enum { DTA_BWD_DELTA = 1, DTA_BWD_DQ = 2, DTA_BWD_DKDV = 4, DTA_BWD_ALL = 7 };

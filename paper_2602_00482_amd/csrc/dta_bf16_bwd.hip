@@ -73,8 +73,8 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
     const int32_t* __restrict__ kend, const uint16_t* __restrict__ q,
     const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const uint16_t* __restrict__ d_o, const float* __restrict__ lse,
-    const float* __restrict__ neg_delta, uint16_t* __restrict__ dq, int Hq, int Hkv, int HB,
-    int hblocks, float scale) {
+    const uint16_t* __restrict__ o, float* __restrict__ neg_delta, float* __restrict__ neg_lse_s,
+    uint16_t* __restrict__ dq, int Hq, int Hkv, int HB, int hblocks, float scale) {
   __shared__ __attribute__((aligned(1024))) uint16_t Ks[2][kTileElems];
   __shared__ __attribute__((aligned(1024))) uint16_t Vs[2][kTileElems];
   __shared__ __attribute__((aligned(16))) int32_t kendS[2][kKeyChunk];
@@ -99,6 +99,12 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
   const size_t rh = (size_t)qrow * Hq + h;
   bf16x8 Qr[kReg], dOr[kReg];
   uint16_t* stash = &stashS[w][0][l * 8];
+  // With o != nullptr this launch also does the work of delta_bf16_kernel for
+  // its rows (every (row, q head) belongs to exactly one lane pair of one
+  // block): D = dO . O, summed in that kernel's order so that the value is the
+  // same to the last bit, and the two row statistics are left in the workspace
+  // for the dK/dV launch that follows.
+  float dpart[8];
   {
     const uint16_t* qp = q + rh * kHeadDim + 8 * hh;
     const uint16_t* dop = d_o + rh * kHeadDim + 8 * hh;
@@ -106,6 +112,13 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
     for (int ks = 0; ks < 8; ++ks) {
       const bf16x8 qx = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
       const bf16x8 dx = *reinterpret_cast<const bf16x8*>(dop + 16 * ks);
+      if (o != nullptr) {
+        const bf16x8 ox = *reinterpret_cast<const bf16x8*>(o + rh * kHeadDim + 8 * hh + 16 * ks);
+        float s = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s = fmaf((float)ox[e], (float)dx[e], s);
+        dpart[ks] = s;
+      }
       if (ks < kReg) {
         Qr[ks < kReg ? ks : 0] = qx;
         dOr[ks < kReg ? ks : 0] = dx;
@@ -125,7 +138,23 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
   };
   // accumulator start values of this lane's query row: the scores start from
   // -lse/scale so that P = exp(scale * acc), dP from -delta so that dS = P * acc
-  const float nlse = -lse[rh] / scale, ndlt = neg_delta[rh];
+  const float nlse = -lse[rh] / scale;
+  float ndlt;
+  if (o != nullptr) {
+    // delta_bf16_kernel's tree over 16 lanes of 8 elements: lane 2*ks + hh there
+    // is k-step ks of lane half hh here
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) dpart[ks] += __shfl_xor(dpart[ks], 32);
+    const float d = ((dpart[0] + dpart[1]) + (dpart[2] + dpart[3])) +
+                    ((dpart[4] + dpart[5]) + (dpart[6] + dpart[7]));
+    ndlt = -d;
+    if (hh == 0 && row_base + c < tile.t1) {
+      neg_delta[rh] = ndlt;
+      neg_lse_s[rh] = -lse[rh] * (1.f / scale);
+    }
+  } else {
+    ndlt = neg_delta[rh];
+  }
 
   f32x16 dQ[4];
 #pragma unroll
@@ -592,7 +621,9 @@ int launch_bwd_bf16(const LaunchArgs& a) {
   const size_t qblocks = a.sched->q_tiles.size() * (size_t)a.p.n_kv_heads * (size_t)a.tc.hblocks;
   const size_t kblocks = a.sched->kv_items.size() * (size_t)a.p.n_kv_heads;
   if (qblocks == 0 || qblocks > 0x7fffffffu || kblocks > 0x7fffffffu) return DTA_ERR_UNSUPPORTED;
-  if (a.stages & DTA_BWD_DELTA) {
+  // the dQ launch computes the row statistics itself when both stages are asked for
+  const bool fused_delta = (a.stages & DTA_BWD_DELTA) && (a.stages & DTA_BWD_DQ);
+  if ((a.stages & DTA_BWD_DELTA) && !fused_delta) {
     delta_bf16_kernel<<<(unsigned)((rows + 15) / 16), 256, 0, st>>>(
         (const uint16_t*)a.o + row0 * kHeadDim, (const uint16_t*)a.d_o + row0 * kHeadDim,
         a.lse_in + row0, a.delta + row0, a.lse2 + row0, 1.f / a.p.softmax_scale, rows);
@@ -601,7 +632,8 @@ int launch_bwd_bf16(const LaunchArgs& a) {
   if (a.stages & DTA_BWD_DQ) {
     dq_bf16_kernel<<<(unsigned)qblocks, kDqThreads, 0, st>>>(
         a.sched->d_q_tiles, a.sched->d_segs, a.d_kend, (const uint16_t*)a.q, (const uint16_t*)a.k,
-        (const uint16_t*)a.v, (const uint16_t*)a.d_o, a.lse_in, a.delta, (uint16_t*)a.dq,
+        (const uint16_t*)a.v, (const uint16_t*)a.d_o, a.lse_in,
+        fused_delta ? (const uint16_t*)a.o : nullptr, a.delta, a.lse2, (uint16_t*)a.dq,
         a.p.n_q_heads, a.p.n_kv_heads, a.tc.hb, a.tc.hblocks, a.p.softmax_scale);
     { int ls = launch_status(__func__); if (ls != DTA_OK) return ls; }
   }

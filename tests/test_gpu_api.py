@@ -50,6 +50,17 @@ def test_staged_backward_equals_one_call_and_is_reproducible(dtype, d):
     torch.cuda.synchronize()
     for a, b in zip(ref, (dq, dk, dv)):
         assert torch.equal(a, b)
+    # asked for together, the dQ launch computes the row statistics itself and leaves
+    # them in the workspace for a later dK/dV call: same bits again
+    ws.fill_(0xff)
+    dq, dk, dv = (torch.full_like(a, float("nan")) for a in ref)
+    args = (tree, p, t["q"], t["k"], t["v"], o, lse, t["do"], dq, dk, dv, ws)
+    dta.tree_attn_bwd(*args, stages=dta.BWD_DELTA | dta.BWD_DQ)
+    assert torch.isnan(dk).all()
+    dta.tree_attn_bwd(*args, stages=dta.BWD_DKDV)
+    torch.cuda.synchronize()
+    for a, b in zip(ref, (dq, dk, dv)):
+        assert torch.equal(a, b)
     tree.destroy()
 
 
