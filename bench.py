@@ -172,6 +172,24 @@ class Runner:
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / steps
 
+    def time_tree_build(self, reps=15):
+        """Host side of a step on an idle GPU: dta_tree_build, then the tile schedule
+        and the metadata upload (dta_tree_attn_prepare).  Median and min, in ms."""
+        dta, torch = self.dta, self.torch
+        torch.cuda.synchronize()
+        b, p = [], []
+        for _ in range(reps):
+            t0 = time.perf_counter()
+            tree = dta.tree_build(self.parent, self.seg)
+            t1 = time.perf_counter()
+            tree.prepare(self.params)
+            t2 = time.perf_counter()
+            tree.destroy()
+            b.append((t1 - t0) * 1e3)
+            p.append((t2 - t1) * 1e3)
+        return {"tree_build_ms": {"median": float(np.median(b)), "min": float(np.min(b))},
+                "schedule_and_upload_ms": {"median": float(np.median(p)), "min": float(np.min(p))}}
+
     def time_kernels(self, iters):
         """Average duration of each launch, HIP events on the launch stream."""
         dta, torch = self.dta, self.torch
@@ -185,18 +203,19 @@ class Runner:
             "dq": lambda: dta.tree_attn_bwd(*a, stages=dta.BWD_DELTA | dta.BWD_DQ),
             "dkdv": lambda: dta.tree_attn_bwd(*a, stages=dta.BWD_DKDV),
         }
-        out = {}
+        out, out_min = {}, {}
         for name, fn in launches.items():
             fn()
             torch.cuda.synchronize()
-            e0 = torch.cuda.Event(enable_timing=True)
-            e1 = torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(iters):
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(iters + 1)]
+            ev[0].record()
+            for i in range(iters):
                 fn()
-            e1.record()
+                ev[i + 1].record()
             torch.cuda.synchronize()
-            out[name] = e0.elapsed_time(e1) / iters
+            out[name] = ev[0].elapsed_time(ev[iters]) / iters
+            out_min[name] = min(ev[i].elapsed_time(ev[i + 1]) for i in range(iters))
+        self.kernel_ms_min = out_min
         info = tree.info()
         sched = tree.schedule_info(self.params)
         tree.destroy()
@@ -359,6 +378,8 @@ def main():
             "ms_per_step": sec * 1e3, "useful_tflops": useful / sec / 1e12,
             "mfma_frac_of_peak": useful / sec / 1e12 / PEAK_TFLOPS[heads["dtype"]],
             "kernel_ms": {k: round(v, 4) for k, v in kern.items()},
+            "kernel_ms_min": {k: round(v, 4) for k, v in r.kernel_ms_min.items()},
+            "host": dict(r.time_tree_build(), metadata_bytes=sched["metadata_bytes"]),
             "kernel_tflops": {k: pairs * Hq * KERNEL_FLOP_D[k] * d / (kern[k] * 1e-3) / 1e12
                               for k in KERNEL_FLOP_D},
             "schedule": sched,

@@ -89,6 +89,8 @@ typedef struct {
   int64_t bwd_kv_tile_tokens;  /* keys per backward dK/dV work item                           */
   int64_t bwd_work_items;
   int64_t bwd_tile_pairs;      /* (padded key cols) x (query rows streamed)                   */
+  int64_t metadata_bytes;      /* what the first attention call copies to the device for this */
+                               /* configuration: kend[] and the work lists                    */
 } dta_schedule_info_t;
 
 typedef struct {

@@ -49,7 +49,7 @@ class _TreeLayout(C.Structure):
 class _ScheduleInfo(C.Structure):
     _fields_ = [(n, C.c_int64) for n in (
         "fwd_q_tile_tokens", "fwd_work_items", "fwd_tile_pairs",
-        "bwd_kv_tile_tokens", "bwd_work_items", "bwd_tile_pairs")]
+        "bwd_kv_tile_tokens", "bwd_work_items", "bwd_tile_pairs", "metadata_bytes")]
 
 
 class AttnParams(C.Structure):

@@ -456,6 +456,10 @@ int dta_tree_schedule_info(dta_tree_t* tree, const dta_attn_params_t* params,
     out->bwd_kv_tile_tokens = tc.bn;
     out->bwd_work_items = (int64_t)s.kv_items.size();
     out->bwd_tile_pairs = s.bwd_tile_pairs;
+    out->metadata_bytes =
+        (int64_t)(tree->token_kend.size() * sizeof(int32_t) + s.q_tiles.size() * sizeof(dta::QTile) +
+                  s.segs.size() * sizeof(dta::KeySeg) + s.kv_tiles.size() * sizeof(dta::KvTile) +
+                  s.kv_items.size() * sizeof(dta::KvItem) + s.kv_reduce.size() * sizeof(dta::KvReduce));
   } catch (const std::bad_alloc&) {
     return DTA_ERR_ALLOC;
   }
