@@ -20,12 +20,19 @@ size_t delta_bytes(const dta_tree* tree, const dta_attn_params_t* p) {
   return round_up((size_t)tree->info.n_tokens * (size_t)p->n_q_heads * sizeof(float), 256);
 }
 
-// delta plus, in bf16 mode, the rescaled lse and the partial sums of split key tiles (building the
-// host schedule if this head configuration has not been seen yet)
+// ticket counters of the kernels that draw their work items from queues: one int per kv head
+// for each of two kernels
+size_t ticket_bytes(const dta_attn_params_t* p) {
+  return round_up(2 * (size_t)p->n_kv_heads * sizeof(int), 256);
+}
+
+// delta plus, in bf16 mode, the rescaled lse, the ticket counters and the partial sums of split
+// key tiles (building the host schedule if this head configuration has not been seen yet)
 size_t bwd_workspace_bytes(dta_tree* tree, const dta::TileChoice& tc, const dta_attn_params_t* p) {
   size_t bytes = delta_bytes(tree, p);
   if (p->dtype == DTA_BF16) {
     bytes += delta_bytes(tree, p);   // lse in log2 units, same shape as delta
+    bytes += ticket_bytes(p);
     try {
       std::lock_guard<std::mutex> lock(tree->mu);
       bytes += dta::partial_bytes(
@@ -381,7 +388,8 @@ int dta_tree_attn_bwd_stages(dta_tree_t* tree, const dta_attn_params_t* params, 
   a.dv = dv;
   a.delta = (float*)workspace;
   a.lse2 = (float*)((char*)workspace + delta_bytes(tree, params));
-  a.partial = (float*)((char*)workspace + 2 * delta_bytes(tree, params));
+  a.tickets = (int*)((char*)workspace + 2 * delta_bytes(tree, params));
+  a.partial = (float*)((char*)workspace + 2 * delta_bytes(tree, params) + ticket_bytes(params));
   a.stages = stage_mask;
   a.row_begin = 0;
   a.row_end = tree->info.n_tokens;
@@ -476,7 +484,8 @@ int dta_tree_attn_bwd_segment(dta_tree_t* tree, const dta_attn_params_t* params,
   a.dv_acc = dv_acc;
   a.delta = (float*)workspace;
   a.lse2 = (float*)((char*)workspace + delta_bytes(tree, params));
-  a.partial = (float*)((char*)workspace + 2 * delta_bytes(tree, params));
+  a.tickets = (int*)((char*)workspace + 2 * delta_bytes(tree, params));
+  a.partial = (float*)((char*)workspace + 2 * delta_bytes(tree, params) + ticket_bytes(params));
   a.stages = DTA_BWD_ALL;
   a.row_begin = t_begin;
   a.row_end = t_end;

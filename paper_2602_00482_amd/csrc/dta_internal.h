@@ -77,6 +77,7 @@ struct Schedule {
   std::vector<KvItem> kv_items;
   std::vector<KvReduce> kv_reduce;
   int64_t n_slots = 0;
+  int64_t kv_item_iters = 0;       // sum over kv_items of (it_end - it_begin)
   int64_t fwd_tile_pairs = 0, bwd_tile_pairs = 0;
   // device copies: one allocation (d_blob, owned, released with the tree) that
   // the typed pointers below point into
@@ -115,6 +116,10 @@ struct dta_tree {
 
 namespace dta {
 
+// Resident blocks of a launch whose blocks draw work items from queues: the
+// 256 CUs of an MI355X times the blocks of that kernel that fit on a CU.
+constexpr int kNumCUs = 256;
+
 // Host: build (or fetch) the schedule for tile sizes (bm, bn).
 Schedule& get_schedule(dta_tree* tree, int bm, int bn, int hkv, int group);
 // Same for a segment call on rows [t_begin, t_end), which must lie inside one
@@ -147,6 +152,7 @@ struct LaunchArgs {
   float* lse_out;
   float* delta;  // workspace: D[t,h] = dO.O
   float* lse2;   // workspace (bf16 path): -lse / softmax_scale, written with delta (there: -D)
+  int* tickets;    // workspace (bf16 path): 2 x n_kv_heads work-queue counters
   float* partial;  // workspace: fp32 partial dK/dV of split key tiles
   // segment calls: rows [row_begin, row_end) only, and dK/dV are ADDED to these
   // fp32 [T,Hkv,d] accumulators instead of written to dk/dv (null otherwise)

@@ -267,6 +267,7 @@ Schedule& get_schedule(dta_tree* tree, int bm, int bn, int hkv, int group) {
                   t.q_begin};
         s.kv_items.push_back(it);
         icost.push_back(it.it_end - it.it_begin);
+        s.kv_item_iters += it.it_end - it.it_begin;
       }
       if (nparts > 1) s.n_slots += nparts;
     }
@@ -355,6 +356,7 @@ Schedule& get_segment_schedule(dta_tree* tree, int bm, int bn, int hkv, int grou
   for (const KvTile& t : s.kv_tiles) {
     const int64_t iters = (int64_t)((t.q_end - t.q_begin + kChunkRows - 1) / kChunkRows) * group;
     s.kv_items.push_back(KvItem{t.k0, t.k1, t.q_end, t.q_full_end, 0, (int32_t)iters, -1, t.q_begin});
+    s.kv_item_iters += iters;
   }
   return s;
 }
