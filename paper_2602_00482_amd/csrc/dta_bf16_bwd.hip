@@ -20,6 +20,7 @@
 
 #include "dta_internal.h"
 #include "dta_mfma.h"
+#include "dta_queue.h"
 #include "dta_tile_walk.h"
 
 namespace dta {
@@ -332,41 +333,11 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
 
   // Which (work item, kv head) this block works on.  tickets == nullptr: the
   // block index says so, one item per block.  Otherwise the launch is a fixed
-  // number of resident blocks that draw items from one queue per kv head
-  // (tickets[head] counts the items handed out, longest first): a block drains
-  // the queue of its home head, blockIdx.x % Hkv, which keeps the head's rows in
-  // the L2 of the XCD the block runs on (blocks are placed round-robin over the
-  // XCDs), and when that queue is empty it takes from the next heads' queues, so
-  // that XCDs that run faster, or finish early, take work from the others.
-  int queue = blockIdx.x % Hkv;
-  int pending = 0;   // thread 0: ticket already drawn from `queue` (see below)
-  // Called by every thread at the same point; returns false when all queues are
-  // empty.  Every call either hands out an item or moves on to the next queue,
-  // and there are Hkv queues: it ends.  With have_pending, thread 0 has already
-  // drawn the first ticket (the draw is started before the stores at the end of
-  // an item, so that its round trip is covered by them).
-  auto draw = [&](int& item, int& head, bool have_pending) {
-    __syncthreads();   // everyone is done with the previous item's LDS data and next_item
-    if (threadIdx.x == 0) {
-      int it = -1, q = queue;
-      int t = have_pending ? pending : atomicAdd(&tickets[q], 1);
-      for (int tries = 1;; ++tries) {
-        if (t < n_items) { it = t; break; }
-        if (tries == Hkv) break;
-        q = q + 1 == Hkv ? 0 : q + 1;
-        t = atomicAdd(&tickets[q], 1);
-      }
-      next_item[0] = it;
-      next_item[1] = q;
-    }
-    __syncthreads();
-    item = __builtin_amdgcn_readfirstlane(next_item[0]);
-    head = __builtin_amdgcn_readfirstlane(next_item[1]);
-    queue = head;
-    return item >= 0;
-  };
+  // number of resident blocks that draw items from one queue per kv head.
+  ItemQueues queues;
+  queues.init(tickets, n_items, Hkv);
   int item_idx = blockIdx.x / Hkv, g_idx = blockIdx.x % Hkv;
-  if (tickets != nullptr && !draw(item_idx, g_idx, false)) return;
+  if (tickets != nullptr && !queues.draw(next_item, item_idx, g_idx, false)) return;
   for (;;) {
   const KvItem tile = items[item_idx];
   const int g = g_idx;
@@ -567,7 +538,7 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
     step(it, std::integral_constant<int, 0>{});
     if (it + 1 < total) step(it + 1, std::integral_constant<int, 1>{});
   }
-  if (tickets != nullptr && threadIdx.x == 0) pending = atomicAdd(&tickets[queue], 1);
+  if (tickets != nullptr) queues.prefetch();
 
   if (tile.slot >= 0) {
     // one of several items of this key tile: fp32 partial sums, [dK | dV] x 128 keys x 128
@@ -620,7 +591,7 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
         *reinterpret_cast<bf16x4*>(dv + base + 32 * dmb + 8 * v4) = rv;
       }
   }
-  if (tickets == nullptr || !draw(item_idx, g_idx, true)) break;
+  if (tickets == nullptr || !queues.draw(next_item, item_idx, g_idx, true)) break;
   }   // next item
 }
 
