@@ -90,7 +90,7 @@ class Runner:
         dta = self.dta
         tree = dta.tree_build(self.parent, self.seg)
         tree.prepare(self.params)
-        dta.tree_attn_fwd(tree, self.params, self.q, self.k, self.v, self.o, self.lse)
+        dta.tree_attn_fwd(tree, self.params, self.q, self.k, self.v, self.o, self.lse, self.ws)
         dta.tree_attn_bwd(tree, self.params, self.q, self.k, self.v, self.o, self.lse, self.do,
                           self.dq, self.dk, self.dv, self.ws)
         return tree
@@ -198,7 +198,7 @@ class Runner:
         a = (tree, self.params, self.q, self.k, self.v, self.o, self.lse, self.do,
              self.dq, self.dk, self.dv, self.ws)
         launches = {
-            "fwd": lambda: dta.tree_attn_fwd(tree, self.params, self.q, self.k, self.v, self.o, self.lse),
+            "fwd": lambda: dta.tree_attn_fwd(tree, self.params, self.q, self.k, self.v, self.o, self.lse, self.ws),
             # as the step issues it: the dQ launch also computes the row statistics D = dO.O
             "dq": lambda: dta.tree_attn_bwd(*a, stages=dta.BWD_DELTA | dta.BWD_DQ),
             "dkdv": lambda: dta.tree_attn_bwd(*a, stages=dta.BWD_DKDV),

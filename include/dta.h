@@ -137,7 +137,10 @@ void dta_tree_destroy(dta_tree_t* tree);
 
 /* Bytes of device workspace dta_tree_attn_fwd (is_bwd = 0) or dta_tree_attn_bwd
  * (is_bwd != 0) needs; 0 on invalid arguments.  The workspace must be 256-byte
- * aligned; its contents need not be preserved between calls. */
+ * aligned; its contents need not be preserved between calls.  Calls that may
+ * overlap in time (different streams) need a workspace each.  The forward's
+ * (a few hundred bytes of work-queue counters in bf16 mode, none in fp32 mode)
+ * is optional, see dta_tree_attn_fwd. */
 size_t dta_tree_attn_workspace_bytes(const dta_tree_t* tree, const dta_attn_params_t* params,
                                      int is_bwd);
 
@@ -157,7 +160,11 @@ int dta_tree_attn_prepare(dta_tree_t* tree, const dta_attn_params_t* params);
  *   q : device [T,Hq,d]   k,v : device [T,Hkv,d]   (dtype per params)
  *   o : device [T,Hq,d] out, same dtype (round to nearest even)
  *   lse : device [T,Hq] fp32 out (natural log)
- *   workspace : device, >= dta_tree_attn_workspace_bytes(tree, params, 0) (may be NULL if that is 0)
+ *   workspace : device, >= dta_tree_attn_workspace_bytes(tree, params, 0) and 256-byte
+ *               aligned, or NULL / smaller: then the launch hands one work item to
+ *               each block instead of letting resident blocks draw items from
+ *               queues, which is a few per cent slower on large inputs and gives
+ *               the same bits
  *   hip_stream : a hipStream_t (NULL = default stream)
  * bf16 mode multiplies in bf16 on the matrix cores and accumulates / does the
  * softmax in fp32; fp32 mode is fp32 throughout.

@@ -243,6 +243,10 @@ def tree_attn_fwd(tree: Tree, params: AttnParams, q, k, v, o=None, lse=None, wor
         lse = torch.empty((T, params.n_q_heads), dtype=torch.float32, device=q.device)
     _check_tensor(o, "o", q.shape, dt)
     _check_tensor(lse, "lse", (T, params.n_q_heads), torch.float32)
+    if workspace is None:
+        need = workspace_bytes(tree, params, False)
+        if need:
+            workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     st = load_library().dta_tree_attn_fwd(tree.handle, C.byref(params), _ptr(q), _ptr(k), _ptr(v),
                                           _ptr(o), _ptr(lse), _ptr(workspace), ws_bytes, _stream())

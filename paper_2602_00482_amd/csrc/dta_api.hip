@@ -306,7 +306,7 @@ size_t dta_tree_attn_workspace_bytes(const dta_tree_t* tree, const dta_attn_para
                                      int is_bwd) {
   dta::TileChoice tc;
   if (!tree || dta::choose_tiles(params, &tc) != DTA_OK) return 0;
-  if (!is_bwd) return 0;
+  if (!is_bwd) return params->dtype == DTA_BF16 ? ticket_bytes(params) : 0;
   return bwd_workspace_bytes(const_cast<dta_tree*>(tree), tc, params);
 }
 
@@ -322,8 +322,6 @@ int dta_tree_attn_prepare(dta_tree_t* tree, const dta_attn_params_t* params) {
 int dta_tree_attn_fwd(dta_tree_t* tree, const dta_attn_params_t* params, const void* q,
                       const void* k, const void* v, void* o, float* lse, void* workspace,
                       size_t workspace_bytes, void* hip_stream) {
-  (void)workspace;
-  (void)workspace_bytes;
   if (!tree || !params) return DTA_ERR_INVALID_ARG;
   dta::TileChoice tc;
   int st = dta::choose_tiles(params, &tc);
@@ -344,6 +342,11 @@ int dta_tree_attn_fwd(dta_tree_t* tree, const dta_attn_params_t* params, const v
   a.v = v;
   a.o_out = o;
   a.lse_out = lse;
+  // optional: with room for the work-queue counters the bf16 forward may run as
+  // resident blocks drawing items from queues
+  if (params->dtype == DTA_BF16 && workspace && ((uintptr_t)workspace & 255u) == 0 &&
+      workspace_bytes >= ticket_bytes(params))
+    a.tickets = (int*)workspace;
   a.row_begin = 0;
   a.row_end = tree->info.n_tokens;
   a.stream = hip_stream;

@@ -17,6 +17,7 @@
 
 #include "dta_internal.h"
 #include "dta_mfma.h"
+#include "dta_queue.h"
 #include "dta_tile_walk.h"
 
 namespace dta {
@@ -34,18 +35,28 @@ __device__ __forceinline__ float max_across_halves(float x) {
   return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
-__global__ __launch_bounds__(kThreads) void fwd_bf16_kernel(
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void fwd_bf16_kernel(
     const QTile* __restrict__ tiles, const KeySeg* __restrict__ segs,
     const int32_t* __restrict__ kend, const uint16_t* __restrict__ q,
     const uint16_t* __restrict__ k, const uint16_t* __restrict__ v, uint16_t* __restrict__ o,
-    float* __restrict__ lse, int Hq, int Hkv, int HB, int hblocks, float scale) {
+    float* __restrict__ lse, int Hq, int Hkv, int HB, int hblocks, float scale,
+    int* __restrict__ tickets, int n_items) {
   __shared__ __attribute__((aligned(1024))) uint16_t Ks[2][kTileElems];
   __shared__ __attribute__((aligned(1024))) uint16_t Vs[2][kTileElems];
   __shared__ __attribute__((aligned(16))) int32_t kendS[2][kKeyChunk];
+  __shared__ int next_item[2];
 
-  const int inner = blockIdx.x % (Hkv * hblocks);
-  const QTile tile = tiles[blockIdx.x / (Hkv * hblocks)];
-  const int g = inner % Hkv, hblk = inner / Hkv;
+  // tickets == nullptr: one (tile, kv head, head block) per block, from the block
+  // index.  Otherwise resident blocks that draw (tile, head block) items from one
+  // queue per kv head.
+  ItemQueues queues;
+  queues.init(tickets, n_items, Hkv);
+  int item_idx = blockIdx.x / (Hkv * hblocks) * hblocks + (blockIdx.x % (Hkv * hblocks)) / Hkv;
+  int g_idx = blockIdx.x % Hkv;
+  if (tickets != nullptr && !queues.draw(next_item, item_idx, g_idx, false)) return;
+  for (;;) {
+  const QTile tile = tiles[item_idx / hblocks];
+  const int g = g_idx, hblk = item_idx % hblocks;
   const int G = Hq / Hkv;
   const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
   const int c = l & 31, hh = l >> 5;
@@ -191,6 +202,7 @@ __global__ __launch_bounds__(kThreads) void fwd_bf16_kernel(
   }
 
   // ---- normalise and store
+  if (tickets != nullptr) queues.prefetch();
   const float lt = lsum + __shfl_xor(lsum, 32);
   const float inv = 1.f / lt;
   const int token = row_base + c;
@@ -207,6 +219,14 @@ __global__ __launch_bounds__(kThreads) void fwd_bf16_kernel(
       }
     if (hh == 0) lse[(size_t)token * Hq + h] = (m * sc + log2f(lt)) * kLn2;
   }
+  if (tickets == nullptr || !queues.draw(next_item, item_idx, g_idx, true)) break;
+  }   // next item
+}
+
+// Sets n ints to zero (the ticket counters; a fill kernel rather than a memset
+// so that the launch sequence can be captured in a graph).
+__global__ void zero_i32_kernel(int* __restrict__ p, int n) {
+  for (int i = threadIdx.x; i < n; i += blockDim.x) p[i] = 0;
 }
 
 }  // namespace
@@ -216,10 +236,18 @@ int launch_fwd_bf16(const LaunchArgs& a) {
   clear_hip_error();
   const size_t blocks = a.sched->q_tiles.size() * (size_t)a.p.n_kv_heads * (size_t)a.tc.hblocks;
   if (blocks == 0 || blocks > 0x7fffffffu) return DTA_ERR_UNSUPPORTED;
-  fwd_bf16_kernel<<<(unsigned)blocks, kThreads, 0, st>>>(
+  // With a workspace for the counters and enough items, resident blocks draw the
+  // items from per-head queues (see dta_queue.h); otherwise one block per item.
+  const bool queues = a.tickets != nullptr && blocks >= 8 * (size_t)kNumCUs;
+  if (queues) {
+    zero_i32_kernel<<<1, 256, 0, st>>>(a.tickets, a.p.n_kv_heads);
+    { int ls = launch_status(__func__); if (ls != DTA_OK) return ls; }
+  }
+  fwd_bf16_kernel<<<(unsigned)(queues ? (size_t)kNumCUs : blocks), kThreads, 0, st>>>(
       a.sched->d_q_tiles, a.sched->d_segs, a.d_kend, (const uint16_t*)a.q, (const uint16_t*)a.k,
       (const uint16_t*)a.v, (uint16_t*)a.o_out, a.lse_out, a.p.n_q_heads, a.p.n_kv_heads, a.tc.hb,
-      a.tc.hblocks, a.p.softmax_scale);
+      a.tc.hblocks, a.p.softmax_scale, queues ? a.tickets : nullptr,
+      (int)(a.sched->q_tiles.size() * (size_t)a.tc.hblocks));
   return launch_status(__func__);
 }
 

@@ -184,3 +184,25 @@ def test_results_do_not_depend_on_which_block_draws_which_item():
     _, _, _, b = _run(6)
     for n in ("o", "lse", "dq", "dk", "dv"):
         assert torch.equal(a[n], b[n]), n
+
+
+def test_forward_without_workspace_gives_the_same_bits():
+    """The forward's workspace is optional: without it the launch hands one item
+    to each block, with it (configuration 2 has enough items) resident blocks
+    draw the items from queues.  Same arithmetic per item, so the same bits."""
+    parent, seg, meta = config_tree(2)
+    h = config_heads(2)
+    Hq, Hkv, d = h["n_q_heads"], h["n_kv_heads"], h["head_dim"]
+    T = int(seg.sum())
+    g = torch.Generator(device="cuda")
+    g.manual_seed(7)
+    mk = lambda heads: torch.randn((T, heads, d), generator=g, device="cuda").to(torch.bfloat16)
+    q, k, v = mk(Hq), mk(Hkv), mk(Hkv)
+    p = dta.AttnParams(Hq, Hkv, d, 1.0 / math.sqrt(d), dta.BF16)
+    tree = dta.tree_build(parent, seg)
+    assert dta.workspace_bytes(tree, p, False) > 0
+    o1, l1 = dta.tree_attn_fwd(tree, p, q, k, v)                       # binding allocates the workspace
+    o2, l2 = dta.tree_attn_fwd(tree, p, q, k, v, workspace=torch.empty(0, dtype=torch.uint8, device="cuda"))
+    torch.cuda.synchronize()
+    tree.destroy()
+    assert torch.equal(o1, o2) and torch.equal(l1, l2)

@@ -145,7 +145,9 @@ def test_error_codes():
         assert err.value.status == want
         assert dta.workspace_bytes(tree, bad, True) == 0
     good = dta.AttnParams(4, 2, 128, 1.0, dta.BF16)
-    assert dta.workspace_bytes(tree, good, False) == 0
+    # the forward's (optional) workspace: work-queue counters in bf16 mode only
+    assert dta.workspace_bytes(tree, good, False) == 256
+    assert dta.workspace_bytes(tree, dta.AttnParams(4, 2, 128, 1.0, dta.F32), False) == 0
     assert dta.workspace_bytes(tree, good, True) >= 7 * 4 * 4
     # null tensors are rejected before anything touches the device
     z = C.c_void_p(0)
