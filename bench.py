@@ -119,10 +119,10 @@ class Runner:
             stack.extend((c, False) for c in reversed(kids[u]))
         return calls
 
-    def step_segments(self, calls):
+    def step_segments(self, calls, tree=None):
         """The same work as step(), issued segment by segment in push / pop order."""
         dta = self.dta
-        tree = dta.tree_build(self.parent, self.seg)
+        tree = dta.tree_build(self.parent, self.seg) if tree is None else tree
         self.dk_acc.zero_()
         self.dv_acc.zero_()
         for tag, t0, t1 in calls:
@@ -156,6 +156,37 @@ class Runner:
         sec = (time.perf_counter() - t0) / steps
         del self.dk_acc, self.dv_acc
         return sec, len(calls)
+
+    def time_segment_graph(self, steps, calls=None):
+        """The same call sequence on ONE tree, captured in a HIP graph after an eager
+        pass (which builds and uploads the segment schedules) and replayed: what an
+        executor pays when the layers of a model reuse the step's tree.  Returns
+        seconds per replay, or None if capture is not available."""
+        torch = self.torch
+        self.dk_acc = torch.empty(self.k.shape, dtype=torch.float32, device="cuda")
+        self.dv_acc = torch.empty_like(self.dk_acc)
+        calls = self.push_pop_order() if calls is None else calls
+        tree = self.dta.tree_build(self.parent, self.seg)
+        sec = None
+        try:
+            self.step_segments(calls, tree)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                self.step_segments(calls, tree)
+            graph.replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                graph.replay()
+            torch.cuda.synchronize()
+            sec = (time.perf_counter() - t0) / steps
+            del graph
+        except RuntimeError as e:
+            print(f"bench.py: graph capture of the segment calls failed: {e}", file=sys.stderr)
+        tree.destroy()
+        del self.dk_acc, self.dv_acc
+        return sec
 
     def time_steps(self, steps, warmup):
         torch = self.torch
@@ -367,6 +398,7 @@ def main():
         if with_segments:
             seg_sec, seg_calls = r.time_segment_steps(max(1, min(5, steps)), 1)
             lo_sec, lo_calls = r.time_segment_steps(max(1, min(5, steps)), 1, r.leaf_order_calls(2048))
+            graph_sec = r.time_segment_graph(max(1, min(5, steps)))
         Hq, d = heads["n_q_heads"], heads["head_dim"]
         pairs = info["unique_pairs"]
         useful = pairs * Hq * 14 * d
@@ -394,6 +426,8 @@ def main():
             res["segment_mode"] = {"ms_per_step": seg_sec * 1e3, "calls": seg_calls,
                                    "useful_tflops": useful / seg_sec / 1e12,
                                    "slowdown_vs_one_launch": seg_sec / sec,
+                                   # the same calls on one tree, captured in a HIP graph and replayed
+                                   "graph_replay_ms": None if graph_sec is None else graph_sec * 1e3,
                                    # the optimised leaf-order schedule, pops chunked at 2048 tokens
                                    "leaf_order_block2048": {"ms_per_step": lo_sec * 1e3, "calls": lo_calls,
                                                             "slowdown_vs_one_launch": lo_sec / sec}}

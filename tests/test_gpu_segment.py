@@ -233,3 +233,52 @@ def test_leaf_order_plan_reproduces_the_whole_tree_results(dtype, d, block):
     for name, ref in (("o", O), ("lse", LSE), ("dq", dQ), ("dk", dK), ("dv", dV)):
         e = rel_err(got[name].double().cpu().numpy(), ref)
         assert e <= TOL[dtype], (name, e)
+
+
+def test_plan_captured_in_a_graph_replays_to_the_eager_result():
+    """An executor that issues hundreds of small segment calls is bound by launch
+    overhead; once the tree's segment schedules are resident (after one eager
+    pass) the calls only enqueue kernels, so the whole sequence can be captured
+    in a HIP graph.  Every replay, with eager work and synchronisation between
+    the replays, must reproduce the eager pass bit for bit."""
+    rng = np.random.default_rng(77)
+    parent, seg = random_tree(rng, 12, 260, n_roots=2)
+    T, Hq, Hkv, d = int(np.sum(seg)), 8, 2, 128
+    inp = make_inputs_numpy(T, Hq, Hkv, d, 5, dtype="bf16")
+    t = {n: torch.from_numpy(a).cuda().to(torch.bfloat16).contiguous() for n, a in inp.items()}
+    tree = dta.tree_build(parent, seg)
+    p = dta.AttnParams(Hq, Hkv, d, 1.0 / math.sqrt(d), dta.BF16)
+    calls = dta.tree_plan(tree, 128)["calls"]
+    o = torch.empty_like(t["q"])
+    lse = torch.empty((T, Hq), dtype=torch.float32, device="cuda")
+    dq = torch.empty_like(t["q"])
+    dk = torch.empty((T, Hkv, d), dtype=torch.float32, device="cuda")
+    dv = torch.empty_like(dk)
+    ws = torch.empty(max(256, dta.workspace_bytes(tree, p, True)), dtype=torch.uint8, device="cuda")
+    outs = (o, lse, dq, dk, dv)
+
+    def run():
+        dk.zero_()
+        dv.zero_()
+        for op, node, t0, t1 in calls:
+            if op == dta.OP_BWD:
+                dta.tree_attn_bwd_segment(tree, p, t0, t1, t["q"], t["k"], t["v"], o, lse, t["do"], dq, dk, dv, ws)
+            else:
+                dta.tree_attn_fwd_segment(tree, p, t0, t1, t["q"], t["k"], t["v"], o, lse)
+
+    run()                                   # eager: builds and uploads every segment schedule
+    torch.cuda.synchronize()
+    want = [x.clone() for x in outs]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    for rep in range(3):
+        for x in outs:
+            x.fill_(float("nan"))           # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for x, w in zip(outs, want):
+            assert torch.equal(x, w), rep
+    del graph
+    tree.destroy()
