@@ -107,6 +107,9 @@ def test_config_counts_and_schedule_cover_every_pair():
         # a tile streams at least the pairs it owns
         assert sch["fwd_tile_pairs"] >= info["unique_pairs"]
         assert sch["bwd_tile_pairs"] >= info["unique_pairs"]
+        # kend[] (4 bytes per token) plus at least 16 bytes per query tile and 32 per key item
+        assert sch["metadata_bytes"] >= 4 * info["n_tokens"] + 16 * sch["fwd_work_items"] + 32 * sch["bwd_work_items"]
+        assert sch["metadata_bytes"] < 64 * info["n_tokens"]
         tree.destroy()
     parent, seg, _ = config_tree(4)
     tree = dta.tree_build(parent, seg)
