@@ -339,8 +339,8 @@ def cpu_oracle_baseline(parent, seg, heads, seed, useful_flop):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration 2..8 of the main line")
     ap.add_argument("--others", type=str, default="3,4,5,6,7,8", help="configs reported as extra objects ('' = none)")
     ap.add_argument("--no-dense", action="store_true")

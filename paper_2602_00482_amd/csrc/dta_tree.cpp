@@ -244,9 +244,14 @@ Schedule& get_schedule(dta_tree* tree, int bm, int bn, int hkv, int group) {
     s.kv_tiles.swap(sorted);
   }
 
-  // ---- dK/dV launch items: cut the longest walks so that the chip stays full.
-  // About 2048 equal items per launch keep 256 CUs x 2 resident blocks busy for
-  // four rounds; a tile is cut only when its walk exceeds 1.5x that share.
+  // ---- dK/dV launch items: cut the longest walks so that no block becomes the
+  // critical path.  The chip holds 512 blocks of this kernel; a piece of a cut
+  // walk is at most 2/3 of the work one of those slots gets on average, and only
+  // walks longer than that are cut.  Finer pieces balance no better and cost
+  // more (every item pays its prologue, the masked steps of its diagonal and,
+  // when cut, fp32 partial sums): with pieces of 1/4 of a slot's share the dK/dV
+  // launch of the 16-response tree (configuration 2) was 5 % slower, coarser
+  // ones (a whole share) let a single piece decide the end of the launch.
   {
     constexpr int kChunkRows = 64;
     auto iters_of = [&](const KvTile& t) {
@@ -254,12 +259,13 @@ Schedule& get_schedule(dta_tree* tree, int bm, int bn, int hkv, int group) {
     };
     int64_t total = 0;
     for (const KvTile& t : s.kv_tiles) total += iters_of(t);
-    const int64_t target = std::max<int64_t>(32, (total * hkv + 2047) / 2048);
+    constexpr int64_t kTargetItems = 768;   // 1.5 pieces per resident block
+    const int64_t target = std::max<int64_t>(32, (total * hkv + kTargetItems - 1) / kTargetItems);
     std::vector<int64_t> icost;
     for (const KvTile& t : s.kv_tiles) {
       const int64_t iters = iters_of(t);
       int64_t nparts = 1;
-      if (2 * iters > 3 * target) nparts = (iters + target - 1) / target;
+      if (iters > target) nparts = (iters + target - 1) / target;
       if (nparts > 1) s.kv_reduce.push_back(KvReduce{t.k0, t.k1, (int32_t)s.n_slots, (int32_t)nparts});
       for (int64_t p = 0; p < nparts; ++p) {
         KvItem it{t.k0, t.k1, t.q_end, t.q_full_end, (int32_t)(iters * p / nparts),
