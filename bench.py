@@ -309,6 +309,37 @@ def mfma_sustained_rate():
             "blocks": n_blocks, "iters": iters}
 
 
+def mfma_valu_overlap():
+    """How much vector-ALU work the hardware hides behind another wave's matrix
+    products on the same SIMD (the library's overlap probe, register work only).
+    The attention kernels' time is products plus exponentials and their
+    bookkeeping, so this bounds what any schedule of them can reach."""
+    import torch
+    import paper_2602_00482_amd as dta
+    n_blocks, iters = 256, 20000          # one block of 8 waves per CU
+    out = torch.empty(n_blocks * 512, dtype=torch.float32, device="cuda")
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+
+    def run(m, v):
+        best = None
+        for _ in range(3):
+            ev[0].record()
+            dta.probe_overlap(n_blocks, m, v, out)
+            ev[1].record()
+            torch.cuda.synchronize()
+            ms = ev[0].elapsed_time(ev[1])
+            best = ms if best is None else min(best, ms)
+        return best
+
+    tm = run(iters, 0)
+    tv = run(0, iters)
+    v_iters = max(1, int(iters * tm / tv))          # same duration for both halves
+    tv = run(0, v_iters)
+    tb = run(iters, v_iters)
+    return {"mfma_only_ms": tm, "exp_only_ms": tv, "both_ms": tb,
+            "hidden_frac_of_shorter": (tm + tv - tb) / min(tm, tv), "both_over_sum": tb / (tm + tv)}
+
+
 def cpu_oracle_baseline(parent, seg, heads, seed, useful_flop):
     """Oracle A (dense per-rollout, fp64 numpy) on a few kv groups of the workload
     (about 10-15 s of CPU work), timed on this machine's host cores and extrapolated
@@ -453,6 +484,7 @@ def main():
     achieved = info["unique_pairs"] * Hq * KERNEL_FLOP_D[dom] * d / (kern[dom] * 1e-3) / 1e12
     peak = PEAK_TFLOPS[heads["dtype"]]
     sustained = mfma_sustained_rate()
+    overlap = mfma_valu_overlap()
     line = {
         "metric": "tree_attn_fwd_bwd_unique_pair_tflops", "value": main_res["useful_tflops"],
         "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -466,7 +498,9 @@ def main():
                      "flop_per_pair_per_head": KERNEL_FLOP_D[dom] * d, "avg_launch_ms": kern[dom],
                      # what this GPU's matrix pipes sustain on products alone (measured just now),
                      # beside the published peak that `frac` is priced against
-                     "mfma_only_probe": sustained, "frac_of_probe": achieved / sustained["tflops"]},
+                     "mfma_only_probe": sustained, "frac_of_probe": achieved / sustained["tflops"],
+                     # one wave's products against another wave's exponentials on the same SIMD
+                     "mfma_valu_overlap_probe": overlap},
         "cpu_baseline": cpu,
         "detail": main_res,
     }

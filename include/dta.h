@@ -389,6 +389,22 @@ void dta_plan_destroy(dta_plan_t* plan);
 int dta_probe_mfma_bf16(int32_t n_blocks, int32_t iters, float* out, uint64_t* ticks, void* hip_stream,
                         int64_t* flop, int32_t* wall_clock_khz);
 
+/*
+ * dta_probe_overlap - measurement helper, not part of the method: how much of
+ * the vector-ALU work of one wave does the hardware hide behind the matrix
+ * products of ANOTHER wave on the same SIMD?  Enqueues n_blocks blocks of 8
+ * waves (two per SIMD): waves 0-3 do mfma_iters x 16 bf16 matrix products, waves
+ * 4-7 do valu_iters x 64 v_exp_f32, all on registers.  The caller times three
+ * launches (valu_iters = 0, mfma_iters = 0, both); `both` between max and sum of
+ * the other two says how far any schedule of the attention kernels, whose time
+ * is products plus exponentials, can go.
+ * out [n_blocks * 512] fp32, device: written.  Asynchronous on hip_stream;
+ * allocates nothing.  INVALID_ARG for a null buffer, n_blocks outside [1, 2^20]
+ * or an iteration count outside [0, 2^24].
+ */
+int dta_probe_overlap(int32_t n_blocks, int32_t mfma_iters, int32_t valu_iters, float* out,
+                      void* hip_stream);
+
 /* Static, human-readable name of a status code. */
 const char* dta_status_string(int status);
 

@@ -22,7 +22,7 @@ exported_symbols = [
     "dta_tree_attn_fwd", "dta_tree_attn_bwd", "dta_tree_attn_bwd_stages",
     "dta_tree_attn_fwd_segment", "dta_tree_attn_bwd_segment", "dta_rollouts_build",
     "dta_rollouts_view", "dta_rollouts_destroy", "dta_rollouts_partition", "dta_tree_plan",
-    "dta_plan_view", "dta_plan_destroy", "dta_probe_mfma_bf16", "dta_status_string",
+    "dta_plan_view", "dta_plan_destroy", "dta_probe_mfma_bf16", "dta_probe_overlap", "dta_status_string",
 ]
 
 
@@ -132,6 +132,8 @@ def load_library():
     lib.dta_probe_mfma_bf16.argtypes = [C.c_int32, C.c_int32, vp, vp, vp, C.POINTER(C.c_int64),
                                         C.POINTER(C.c_int32)]
     lib.dta_probe_mfma_bf16.restype = C.c_int
+    lib.dta_probe_overlap.argtypes = [C.c_int32, C.c_int32, C.c_int32, vp, vp]
+    lib.dta_probe_overlap.restype = C.c_int
     lib.dta_status_string.argtypes = [C.c_int]
     lib.dta_status_string.restype = C.c_char_p
     _lib = lib
@@ -411,3 +413,12 @@ def probe_mfma_bf16(n_blocks: int, iters: int, out, ticks):
     _check(load_library().dta_probe_mfma_bf16(int(n_blocks), int(iters), _ptr(out), _ptr(ticks), _stream(),
                                               C.byref(flop), C.byref(khz)), "dta_probe_mfma_bf16")
     return int(flop.value), int(khz.value)
+
+
+def probe_overlap(n_blocks: int, mfma_iters: int, valu_iters: int, out):
+    """dta_probe_overlap on torch's current stream; out is a device fp32 tensor
+    of n_blocks*512 elements."""
+    if out.numel() < n_blocks * 512:
+        raise ValueError("probe buffer too small")
+    _check(load_library().dta_probe_overlap(int(n_blocks), int(mfma_iters), int(valu_iters), _ptr(out), _stream()),
+           "dta_probe_overlap")

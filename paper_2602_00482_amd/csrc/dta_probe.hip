@@ -60,7 +60,67 @@ __global__ __launch_bounds__(kProbeThreads, 2) void mfma_rate_kernel(float* __re
   }
 }
 
+// Do the matrix products of one wave and the vector-ALU work of ANOTHER wave on
+// the same SIMD overlap?  Block = 8 waves, two per SIMD (wave i runs on SIMD
+// i % 4): waves 0-3 do mfma_iters x 16 independent products, waves 4-7 do
+// valu_iters x 64 independent v_exp_f32.  Registers only.  Timed three times by
+// the caller (products only, exponentials only, both), it shows how much of
+// the shorter part the hardware can hide behind the longer one, which bounds
+// what any schedule of the attention kernels can reach.
+constexpr int kOverlapThreads = 512;
+
+__global__ __launch_bounds__(kOverlapThreads) void overlap_kernel(float* __restrict__ out, int mfma_iters,
+                                                                  int valu_iters) {
+  const int w = threadIdx.x >> 6;
+  float acc = 0.f;
+  if (w < 4) {
+    bf16x8 a, b;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      a[e] = (__bf16)(0.01f * (float)(threadIdx.x % 7 + e));
+      b[e] = (__bf16)(0.02f * (float)(threadIdx.x % 5 + e));
+    }
+    f32x16 c[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) c[j][e] = 0.f;
+    for (int it = 0; it < mfma_iters; ++it)
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) c[j] = mfma32(a, b, c[j]);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc += c[j][e];
+  } else {
+    float x[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) x[i] = 0.001f * (float)(threadIdx.x + i);
+    for (int it = 0; it < valu_iters; ++it)
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) x[i] = __builtin_amdgcn_exp2f(-x[i]);   // stays in (0.5, 1]
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc += x[i];
+  }
+  out[(size_t)blockIdx.x * kOverlapThreads + threadIdx.x] = acc;
+}
+
 }  // namespace dta
+
+extern "C" int dta_probe_overlap(int32_t n_blocks, int32_t mfma_iters, int32_t valu_iters, float* out,
+                                 void* hip_stream) {
+  if (n_blocks < 1 || n_blocks > (1 << 20) || mfma_iters < 0 || valu_iters < 0 || mfma_iters > (1 << 24) ||
+      valu_iters > (1 << 24) || !out)
+    return DTA_ERR_INVALID_ARG;
+  (void)hipGetLastError();
+  hipLaunchKernelGGL(dta::overlap_kernel, dim3(n_blocks), dim3(dta::kOverlapThreads), 0, (hipStream_t)hip_stream, out,
+                     mfma_iters, valu_iters);
+  return hipGetLastError() == hipSuccess ? DTA_OK : DTA_ERR_HIP;
+}
 
 extern "C" int dta_probe_mfma_bf16(int32_t n_blocks, int32_t iters, float* out, uint64_t* ticks, void* hip_stream,
                                    int64_t* flop, int32_t* wall_clock_khz) {

@@ -161,3 +161,12 @@ def test_mfma_rate_probe_is_linear_in_its_iteration_count():
     assert float(outs[1].abs().max()) > 0
     assert torch.equal(outs[2], 2 * outs[1])
     assert torch.equal(outs[8], 8 * outs[1])
+
+
+def test_overlap_probe_runs_and_writes_every_element():
+    out = torch.full((2 * 512,), float("nan"), dtype=torch.float32, device="cuda")
+    for m, v in ((3, 0), (0, 3), (3, 3)):
+        out.fill_(float("nan"))
+        dta.probe_overlap(2, m, v, out)
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(out).all())

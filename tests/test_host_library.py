@@ -165,6 +165,10 @@ def test_error_codes():
     assert lib.dta_probe_mfma_bf16(0, 1, one, one, z, None, None) == -1
     assert lib.dta_probe_mfma_bf16(1, 0, one, one, z, None, None) == -1
     assert lib.dta_probe_mfma_bf16(2 ** 20 + 1, 1, one, one, z, None, None) == -1
+    assert lib.dta_probe_overlap(1, 1, 1, z, z) == -1
+    assert lib.dta_probe_overlap(0, 1, 1, one, z) == -1
+    assert lib.dta_probe_overlap(1, -1, 1, one, z) == -1
+    assert lib.dta_probe_overlap(1, 1, 2 ** 24 + 1, one, z) == -1
     lib.dta_tree_destroy(None)
     tree.destroy()
 
