@@ -35,15 +35,21 @@ __device__ __forceinline__ float max_across_halves(float x) {
   return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
+// kCh = keys per streamed chunk (one or two 64-row LDS tiles per operand): one
+// barrier, one round of bookkeeping and one online-softmax step per chunk, so
+// long key intervals run faster with 128, while every interval is padded to a
+// multiple of the chunk, so forests of short segments want 64.
+template <int kCh>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void fwd_bf16_kernel(
     const QTile* __restrict__ tiles, const KeySeg* __restrict__ segs,
     const int32_t* __restrict__ kend, const uint16_t* __restrict__ q,
     const uint16_t* __restrict__ k, const uint16_t* __restrict__ v, uint16_t* __restrict__ o,
     float* __restrict__ lse, int Hq, int Hkv, int HB, int hblocks, float scale,
     int* __restrict__ tickets, int n_items) {
-  __shared__ __attribute__((aligned(1024))) uint16_t Ks[2][kTileElems];
-  __shared__ __attribute__((aligned(1024))) uint16_t Vs[2][kTileElems];
-  __shared__ __attribute__((aligned(16))) int32_t kendS[2][kKeyChunk];
+  constexpr int kSub = kCh / 64;
+  __shared__ __attribute__((aligned(1024))) uint16_t Ks[2][kSub][kTileElems];
+  __shared__ __attribute__((aligned(1024))) uint16_t Vs[2][kSub][kTileElems];
+  __shared__ __attribute__((aligned(16))) int32_t kendS[2][kCh];
   __shared__ int next_item[2];
 
   // tickets == nullptr: one (tile, kv head, head block) per block, from the block
@@ -94,19 +100,26 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
 
   // Chunk i lives in buffer i & 1 and is copied global -> LDS one iteration ahead
   // of its use, so one barrier per chunk is enough.
-  KeyChunks it;
+  KeyChunksT<kCh> it;
   it.init(segs, tile);
   int c0, n, full;
   bool have = it.next(c0, n, full);
   auto issue = [&](int b) {
-    if (!full || n < kKeyChunk) {   // rare: a chunk that needs the visibility mask
-      if (threadIdx.x < kKeyChunk) {   // kendS is indexed by matrix position
-        const int row = row_of_pos(threadIdx.x);
+    if (!full || n < kCh) {   // rare: a chunk that needs the visibility mask
+      if (threadIdx.x < kCh) {   // kendS is indexed by matrix position within each 64-key half
+        const int row = 64 * (threadIdx.x >> 6) + row_of_pos(threadIdx.x & 63);
         kendS[b][threadIdx.x] = row >= n ? 0 : (full ? 0x7fffffff : kend[c0 + row]);
       }
     }
-    tile_async_load<kThreads>(Ks[b], kbase + (size_t)c0 * kv_stride, kv_bytes, n);
-    tile_async_load<kThreads>(Vs[b], vbase + (size_t)c0 * kv_stride, kv_bytes, n);
+#pragma unroll
+    for (int sub = 0; sub < kSub; ++sub) {
+      // a half with no valid key re-reads the chunk's first row (finite data the mask hides)
+      const int nv = n - 64 * sub;
+      const int r0 = nv > 0 ? c0 + 64 * sub : c0;
+      const int nvalid = nv > 0 ? min(nv, 64) : 1;
+      tile_async_load<kThreads>(Ks[b][sub], kbase + (size_t)r0 * kv_stride, kv_bytes, nvalid);
+      tile_async_load<kThreads>(Vs[b][sub], vbase + (size_t)r0 * kv_stride, kv_bytes, nvalid);
+    }
   };
   issue(0);
   int buf = 0;
@@ -116,32 +129,34 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
     async_wait_all();
     __syncthreads();   // chunk `buf` has landed; everyone is done with the other buffer
     const int cc0 = c0;
-    const bool need_mask = !full || n < kKeyChunk;
+    const bool need_mask = !full || n < kCh;
     have = it.next(c0, n, full);
     if (have) issue(buf ^ 1);
-    const uint16_t* Kt = Ks[buf] + rlo;
-    const uint16_t* Vt = Vs[buf] + clo;
+    const uint16_t* Kt = Ks[buf][0] + rlo;
+    const uint16_t* Vt = Vs[buf][0] + clo;
 
     // ---- S^T = K Q^T : 64 keys x 32 queries
-    f32x16 S[2];
+    f32x16 S[2 * kSub];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < 2 * kSub; ++a)
 #pragma unroll
       for (int e = 0; e < 16; ++e) S[a][e] = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      const bf16x8 a0 = tile_row8(Kt, 0, ks);
-      const bf16x8 a1 = tile_row8(Kt, 1, ks);
-      S[0] = mfma32(a0, Qr[ks], S[0]);
-      S[1] = mfma32(a1, Qr[ks], S[1]);
-    }
+    for (int sub = 0; sub < kSub; ++sub)
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        const bf16x8 a0 = tile_row8(Kt + sub * kTileElems, 0, ks);
+        const bf16x8 a1 = tile_row8(Kt + sub * kTileElems, 1, ks);
+        S[2 * sub] = mfma32(a0, Qr[ks], S[2 * sub]);
+        S[2 * sub + 1] = mfma32(a1, Qr[ks], S[2 * sub + 1]);
+      }
 
     // ---- mask: key kv is visible to row t iff kv <= t < kend[kv]; kendS holds
     // 0 for padding keys and INT_MAX for keys every row of the tile sees (those
     // lie before the tile, so the causal test is true for them anyway)
     if (need_mask) {
 #pragma unroll
-      for (int mb = 0; mb < 2; ++mb)
+      for (int mb = 0; mb < 2 * kSub; ++mb)
 #pragma unroll
         for (int e4 = 0; e4 < 4; ++e4) {
           const int kvl0 = 32 * mb + 8 * e4 + 4 * hh;
@@ -149,7 +164,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
           const int kev[4] = {ke.x, ke.y, ke.z, ke.w};
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
-            const bool ok = (cc0 + row_of_acc(mb, 4 * e4 + j, hh) <= qrow) & (qrow < kev[j]);
+            const bool ok = (cc0 + 64 * (mb >> 1) + row_of_acc(mb & 1, 4 * e4 + j, hh) <= qrow) & (qrow < kev[j]);
             S[mb][4 * e4 + j] = ok ? S[mb][4 * e4 + j] : -INFINITY;
           }
         }
@@ -158,7 +173,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
     // ---- online softmax, one query column per lane
     float mx = -INFINITY;
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
+    for (int mb = 0; mb < 2 * kSub; ++mb)
 #pragma unroll
       for (int e = 0; e < 16; ++e) mx = fmaxf(mx, S[mb][e]);
     mx = max_across_halves(mx);
@@ -168,9 +183,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
     m = mnew;
     const float msc = mref * sc;
     float ps = 0.f;
-    bf16x8 Pb[4];
+    bf16x8 Pb[4 * kSub];
 #pragma unroll
-    for (int mb = 0; mb < 2; ++mb) {
+    for (int mb = 0; mb < 2 * kSub; ++mb) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         const float p = __builtin_amdgcn_exp2f(fmaf(S[mb][e], sc, -msc));
@@ -191,13 +206,15 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
 
     // ---- O^T += V^T P^T
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
+    for (int sub = 0; sub < kSub; ++sub)
 #pragma unroll
-      for (int dmb = 0; dmb < 4; ++dmb) {
-        const bf16x8 va = tile_col8(Vt, 16 * kk, 32 * dmb);
-        O[dmb] = mfma32(va, Pb[kk], O[dmb]);
+      for (int kk = 0; kk < 4; ++kk) {
+#pragma unroll
+        for (int dmb = 0; dmb < 4; ++dmb) {
+          const bf16x8 va = tile_col8(Vt + sub * kTileElems, 16 * kk, 32 * dmb);
+          O[dmb] = mfma32(va, Pb[4 * sub + kk], O[dmb]);
+        }
       }
-    }
     buf ^= 1;
   }
 
@@ -243,7 +260,11 @@ int launch_fwd_bf16(const LaunchArgs& a) {
     zero_i32_kernel<<<1, 256, 0, st>>>(a.tickets, a.p.n_kv_heads);
     { int ls = launch_status(__func__); if (ls != DTA_OK) return ls; }
   }
-  fwd_bf16_kernel<<<(unsigned)(queues ? (size_t)kNumCUs : blocks), kThreads, 0, st>>>(
+  // chunk size: 128 keys when padding every key interval to 128 instead of 64 adds
+  // less than 4 % to the keys streamed
+  const bool wide = 2 * a.sched->fwd_chunks128 * 100 <= a.sched->fwd_chunks64 * 104;
+  auto kernel = wide ? fwd_bf16_kernel<128> : fwd_bf16_kernel<64>;
+  kernel<<<(unsigned)(queues ? (size_t)kNumCUs : blocks), kThreads, 0, st>>>(
       a.sched->d_q_tiles, a.sched->d_segs, a.d_kend, (const uint16_t*)a.q, (const uint16_t*)a.k,
       (const uint16_t*)a.v, (uint16_t*)a.o_out, a.lse_out, a.p.n_q_heads, a.p.n_kv_heads, a.tc.hb,
       a.tc.hblocks, a.p.softmax_scale, queues ? a.tickets : nullptr,

@@ -79,6 +79,8 @@ struct Schedule {
   int64_t n_slots = 0;
   int64_t kv_item_iters = 0;       // sum over kv_items of (it_end - it_begin)
   int64_t fwd_tile_pairs = 0, bwd_tile_pairs = 0;
+  // chunks the query tiles stream when every key interval is cut into pieces of 64 / 128 keys
+  int64_t fwd_chunks64 = 0, fwd_chunks128 = 0;
   // device copies: one allocation (d_blob, owned, released with the tree) that
   // the typed pointers below point into
   int device = -1;

@@ -6,11 +6,12 @@
 
 namespace dta {
 
-constexpr int kKeyChunk = 64;  // keys per streamed LDS tile
+constexpr int kKeyChunk = 64;  // keys per LDS tile
 
-// Yields the key intervals of a query tile in 64-key chunks: the pieces of the
-// tile's root path first (root to parent), the tile's own token range last.
-struct KeyChunks {
+// Yields the key intervals of a query tile in chunks of CH keys: the pieces of
+// the tile's root path first (root to parent), the tile's own token range last.
+template <int CH>
+struct KeyChunksT {
   const KeySeg* segs;
   int si, seg_end, t0, t1;
   int cur, end, full;
@@ -27,18 +28,19 @@ struct KeyChunks {
   }
   // number of chunks the walk will yield
   __device__ __forceinline__ static int count(const KeySeg* s, const QTile& t) {
-    int nch = (t.t1 - t.t0 + kKeyChunk - 1) / kKeyChunk;
-    for (int i = t.seg_begin; i < t.seg_end; ++i) nch += (s[i].end - s[i].start + kKeyChunk - 1) / kKeyChunk;
+    int nch = (t.t1 - t.t0 + CH - 1) / CH;
+    for (int i = t.seg_begin; i < t.seg_end; ++i) nch += (s[i].end - s[i].start + CH - 1) / CH;
     return nch;
   }
-  // c0 = first key, n = keys in the chunk (<= 64), is_full = no mask needed
+  // c0 = first key, n = keys in the chunk (<= CH), is_full = no mask needed
   __device__ __forceinline__ bool next(int& c0, int& n, int& is_full) {
     if (si > seg_end) return false;
-    c0 = cur; n = min(kKeyChunk, end - cur); is_full = full;
-    cur += kKeyChunk;
+    c0 = cur; n = min(CH, end - cur); is_full = full;
+    cur += CH;
     if (cur >= end) { ++si; if (si <= seg_end) load_seg(); }
     return true;
   }
 };
+using KeyChunks = KeyChunksT<kKeyChunk>;
 
 }  // namespace dta

@@ -159,6 +159,18 @@ int64_t order_key(int64_t cost) {
 // tiles, so cutting at node boundaries could only add work.  What a mixed tile
 // must not do is let a row see a key outside its own root path: the kernels
 // mask with kend[] wherever a key interval is not visible to every row.
+namespace {
+// adds the chunks a query tile streams, for both chunk sizes of the forward kernel
+void count_chunks(Schedule& s, const QTile& qt) {
+  auto add = [&](int64_t len) {
+    s.fwd_chunks64 += (len + 63) / 64;
+    s.fwd_chunks128 += (len + 127) / 128;
+  };
+  for (int32_t i = qt.seg_begin; i < qt.seg_end; ++i) add(s.segs[(size_t)i].end - s.segs[(size_t)i].start);
+  add(qt.t1 - qt.t0);
+}
+}  // namespace
+
 size_t partial_bytes(const Schedule& s) {
   return (size_t)s.n_slots * (size_t)s.hkv * 2u * (size_t)s.bn * 128u * sizeof(float);
 }
@@ -208,6 +220,7 @@ Schedule& get_schedule(dta_tree* tree, int bm, int bn, int hkv, int group) {
     s.q_tiles.push_back(qt);
     cost.push_back(keys);
     s.fwd_tile_pairs += keys * bm;
+    count_chunks(s, qt);
   }
   {
     std::vector<size_t> order(s.q_tiles.size());
@@ -342,6 +355,7 @@ Schedule& get_segment_schedule(dta_tree* tree, int bm, int bn, int hkv, int grou
     qt.seg_end = (int32_t)s.segs.size();
     s.q_tiles.push_back(qt);
     s.fwd_tile_pairs += (prefix_keys + (t1 - t_begin)) * bm;
+    count_chunks(s, qt);
   }
   std::reverse(s.q_tiles.begin(), s.q_tiles.end());   // the last tile sees the most keys
 
