@@ -47,8 +47,8 @@ KERNEL_FLOP_D = {"fwd": 4, "dq": 6, "dkdv": 8}
 # profiles/*_hbm_traffic.md.  Not measured live.  "dkdv" is the dK/dV stage as timed here:
 # the dK/dV kernel plus the reduction of split tiles.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg2_grpo_single_prompt_tree": {"fwd": 4.54e8, "dq": 1.00e9, "dkdv": 3.21e9},
-    "cfg4_deep_long_context_tree": {"fwd": 1.01e11, "dq": 6.14e10, "dkdv": 4.33e11},
+    "cfg2_grpo_single_prompt_tree": {"fwd": 4.58e8, "dq": 1.00e9, "dkdv": 3.21e9},
+    "cfg4_deep_long_context_tree": {"fwd": 6.36e10, "dq": 6.18e10, "dkdv": 4.22e11},
 }
 
 
