@@ -29,10 +29,12 @@ pytestmark = pytest.mark.gpu
 TOL = 1e-2
 
 
-def _run(cfg):
+def _run(cfg, heads=None):
     parent, seg, meta = config_tree(cfg)
     h = config_heads(cfg)
     Hq, Hkv, d = h["n_q_heads"], h["n_kv_heads"], h["head_dim"]
+    if heads is not None:
+        Hq, Hkv = heads
     T = int(seg.sum())
     g = torch.Generator(device="cuda")
     g.manual_seed(meta["tensor_seed"])
@@ -144,12 +146,15 @@ def test_full_size_sampled_rows_and_invariants(cfg):
     assert ek <= TOL and ev <= TOL
 
 
-@pytest.mark.parametrize("cfg,block", [(2, 0), (3, 2048)])
-def test_full_size_segment_calls_agree_with_the_one_launch_path(cfg, block):
+@pytest.mark.parametrize("cfg,block,heads", [(2, 0, None), (3, 2048, None), (5, 0, (6, 3))])
+def test_full_size_segment_calls_agree_with_the_one_launch_path(cfg, block, heads):
     """The paper's executor order at full size: the calls of dta_tree_plan issued
     one by one on zeroed accumulators, against the one-launch results checked
-    above (both bf16 evaluations of the same sums)."""
-    parent, seg, (Hq, Hkv, d, scale), t = _run(cfg)
+    above (both bf16 evaluations of the same sums).  The last case has three kv
+    heads: its one-launch forward and dK/dV run as resident blocks drawing items
+    from three queues whose home heads do not line up with the 8 XCDs, while the
+    segment calls are small launches with one block per item."""
+    parent, seg, (Hq, Hkv, d, scale), t = _run(cfg, heads)
     T = int(seg.sum())
     p = dta.AttnParams(Hq, Hkv, d, scale, dta.BF16)
     tree = dta.tree_build(parent, seg)
