@@ -395,6 +395,8 @@ def main():
     import torch
     import paper_2602_00482_amd as dta
     from workloads import config_heads, config_tree
+    from paper_2602_00482_amd.build import ensure_built
+    ensure_built()              # builds only if no library is there
     dta.load_library()          # fails loudly if the HIP library is missing
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)

@@ -43,5 +43,11 @@ def build(verbose: bool = False) -> str:
     return LIB_PATH
 
 
+def ensure_built() -> str:
+    """Build only if no library is there (tests, the smoke run and the benchmark
+    call this; whoever changes a source builds explicitly)."""
+    return LIB_PATH if os.path.exists(LIB_PATH) else build()
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
