@@ -13,21 +13,25 @@
 
 namespace dta {
 
-// One forward / dQ work item: BM consecutive packed query tokens [t0, t1).  The
-// keys they can see are the key intervals segs[seg_begin, seg_end) that lie
-// before t0 (pieces of t0's root path) followed by the tile's own range, which
-// always needs the visibility mask  k <= t < kend[k].
-struct QTile {
-  int32_t t0, t1;
-  int32_t seg_begin, seg_end;
-};
-
 // A key interval [start, end) in packed token coordinates.  full != 0 means
 // every query row of the tile sees every key of the interval (no mask needed).
 struct KeySeg {
   int32_t start, end;
   int32_t full;
   int32_t pad;
+};
+
+// One forward / dQ work item: BM consecutive packed query tokens [t0, t1).  The
+// keys they can see are the key intervals segs[seg_begin, seg_end) that lie
+// before t0 (pieces of t0's root path) followed by the tile's own range, which
+// always needs the visibility mask  k <= t < kend[k].
+// The first interval is repeated inside the tile record (first.start == first.end
+// when there is none), so that a block can start its first K/V copy after one
+// dependent read instead of two.
+struct QTile {
+  int32_t t0, t1;
+  int32_t seg_begin, seg_end;
+  KeySeg first;
 };
 
 // One dK/dV work item: BN consecutive packed keys [k0, k1).  The queries the

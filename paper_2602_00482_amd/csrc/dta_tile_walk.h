@@ -24,7 +24,11 @@ struct KeyChunksT {
   }
   __device__ __forceinline__ void init(const KeySeg* s, const QTile& t) {
     segs = s; si = t.seg_begin; seg_end = t.seg_end; t0 = t.t0; t1 = t.t1;
-    load_seg();
+    if (si < seg_end) {   // the first interval travels with the tile record
+      cur = t.first.start; end = t.first.end; full = t.first.full;
+    } else {
+      cur = t0; end = t1; full = 0;
+    }
   }
   // number of chunks the walk will yield
   __device__ __forceinline__ static int count(const KeySeg* s, const QTile& t) {

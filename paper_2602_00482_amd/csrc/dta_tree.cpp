@@ -171,6 +171,14 @@ void count_chunks(Schedule& s, const QTile& qt) {
 }
 }  // namespace
 
+namespace {
+// copies each tile's first key interval into its record
+void fill_first_intervals(Schedule& s) {
+  for (QTile& t : s.q_tiles)
+    t.first = t.seg_begin < t.seg_end ? s.segs[(size_t)t.seg_begin] : KeySeg{t.t0, t.t0, 0, 0};
+}
+}  // namespace
+
 size_t partial_bytes(const Schedule& s) {
   return (size_t)s.n_slots * (size_t)s.hkv * 2u * (size_t)s.bn * 128u * sizeof(float);
 }
@@ -232,6 +240,7 @@ Schedule& get_schedule(dta_tree* tree, int bm, int bn, int hkv, int group) {
     for (size_t i : order) sorted.push_back(s.q_tiles[i]);
     s.q_tiles.swap(sorted);
   }
+  fill_first_intervals(s);
 
   // ---- key tiles (dK/dV)
   cost.clear();
@@ -358,6 +367,7 @@ Schedule& get_segment_schedule(dta_tree* tree, int bm, int bn, int hkv, int grou
     count_chunks(s, qt);
   }
   std::reverse(s.q_tiles.begin(), s.q_tiles.end());   // the last tile sees the most keys
+  fill_first_intervals(s);
 
   // ---- key tiles: the prefix pieces (walk = all rows, no mask beyond padding),
   // then the rows themselves (causal)
