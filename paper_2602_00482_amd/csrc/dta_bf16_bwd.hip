@@ -667,9 +667,9 @@ int launch_bwd_bf16(const LaunchArgs& a) {
     // the others and save the block hand-over, at the price of a barrier pair
     // and an atomic per item and of some L2 locality when work moves between
     // XCDs.  Measured on MI355X (dK/dV launch, queues against blocks): forests
-    // of many medium items gain (9.7 rounds of 300-step items +4 %, 15-33 rounds
-    // of 70-160-step items +0.6...+1.5 %), fewer than 8 rounds lose 1 % to the
-    // extra launch, and long items (1100 steps on average) lose 1.6 %.
+    // of many short items gain (15-33 rounds of 70-160-step items +0.6...+1.5 %,
+    // up to +4 % with finer pieces), fewer than 8 rounds lose 1 % to the extra
+    // launch, and long items (1100 steps on average) lose 1.6 %.
     const size_t resident = 2 * (size_t)kNumCUs;
     const bool queues = kblocks >= 8 * resident &&
                         a.sched->kv_item_iters <= 512 * (int64_t)a.sched->kv_items.size();
