@@ -709,3 +709,70 @@ def test_leaf_first_order_needs_no_anchor_on_a_star():
     ops, pi = S.schedule(parent, seg, 0)
     assert [seg[u] for u in pi] == sorted(seg[1:], reverse=True)       # reversed smaller-tail-first order
     assert [t for t in ops if t[0] == "NOGRAD"] == [("NOGRAD", pi[0], 0, 10)]
+
+
+# ------------------------------------------- gradients of chosen keys (oracle K)
+def test_key_gradients_equal_rollout_expansion_rows():
+    """The per-key oracle (pop step written out key by key) returns exactly the
+    rows of the dense per-rollout oracle's dK/dV, for keys of roots, interior
+    nodes and leaves, in any order, with the rows of a node held in memory all
+    at once or a few at a time."""
+    from oracle import key_gradient as K
+    rng = np.random.default_rng(91)
+    cases = [config_tree(1)[:2]] + [random_tree(rng, int(rng.integers(2, 12)), 9, n_roots=int(rng.integers(1, 3)))
+                                    for _ in range(5)]
+    for ci, (parent, seg) in enumerate(cases):
+        if ci == 0:
+            seg = np.maximum(1, seg // 4)
+        T = int(seg.sum())
+        q, k, v, do = _inputs(T, 4, 2, 8, seed=300 + ci)
+        _, dKa, dVa = A.backward(parent, seg, q, k, v, do, 0.33)
+        keys = rng.permutation(T)[: max(1, T // 3)]
+        for g in range(2):
+            for max_rows in (None, 3):
+                dK, dV, pairs = K.key_gradients(parent, seg, q[:, 2 * g:2 * g + 2], k[:, g], v[:, g],
+                                                do[:, 2 * g:2 * g + 2], 0.33, keys, max_rows=max_rows)
+                assert np.abs(dK - dKa[keys, g]).max() < 1e-11
+                assert np.abs(dV - dVa[keys, g]).max() < 1e-11
+                assert pairs > 0
+
+
+def test_key_gradients_against_finite_differences_of_a_brute_force_objective():
+    """d/dk and d/dv of sum_t O_t . dO_t, with O from the token-by-token pure
+    python forward (no oracle code on the reference side)."""
+    from oracle import key_gradient as K
+    rng = np.random.default_rng(92)
+    parent, seg = random_tree(rng, 6, 4)
+    _, vis, T = _token_tables(parent, seg)
+    q, k, v, do = _inputs(T, 2, 1, 5, seed=17)
+    scale = 0.45
+    keys = np.arange(T)
+    dK, dV, _ = K.key_gradients(parent, seg, q, k[:, 0], v[:, 0], do, scale, keys)
+    f = lambda: float((_brute_forward(vis, q, k, v, scale, 2)[0] * do).sum())
+    eps = 1e-5
+    for arr, grad in ((k, dK), (v, dV)):
+        for _ in range(12):
+            t, j = int(rng.integers(0, T)), int(rng.integers(0, 5))
+            old = arr[t, 0, j]
+            arr[t, 0, j] = old + eps
+            fp = f()
+            arr[t, 0, j] = old - eps
+            fm = f()
+            arr[t, 0, j] = old
+            fd = (fp - fm) / (2 * eps)
+            assert abs(fd - grad[t, j]) < 1e-7 * max(1.0, abs(fd)), (t, j, fd, grad[t, j])
+
+
+def test_key_gradients_of_all_keys_obey_the_column_sum_identity():
+    """Rows of P sum to one, so the dV rows of ALL keys add up to the sum of dO
+    over tokens and the q heads of the group; a key set that leaves tokens out
+    must fall short of it (the function really restricts itself to its keys)."""
+    from oracle import key_gradient as K
+    rng = np.random.default_rng(93)
+    parent, seg = random_tree(rng, 7, 6, n_roots=2)
+    T = int(seg.sum())
+    q, k, v, do = _inputs(T, 3, 1, 6, seed=18)
+    _, dV, _ = K.key_gradients(parent, seg, q, k[:, 0], v[:, 0], do, 0.3, np.arange(T))
+    assert np.abs(dV.sum(axis=0) - do.sum(axis=(0, 1))).max() < 1e-11
+    _, dV_part, _ = K.key_gradients(parent, seg, q, k[:, 0], v[:, 0], do, 0.3, np.arange(1, T))
+    assert np.abs(dV_part - dV[1:]).max() < 1e-12
