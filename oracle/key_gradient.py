@@ -74,7 +74,8 @@ def key_gradients(parent, seg_len, q, k, v, do, scale, keys, device="cpu", max_r
         query_nodes.add(u)
         stack.extend(kids[u])
 
-    slot_of_key = {int(x): i for i, x in enumerate(keys)}
+    slot_of_token = np.full(T, -1, dtype=np.int64)      # position of a token in `keys`, -1 = not requested
+    slot_of_token[keys] = np.arange(len(keys))
     dK = torch.zeros((len(keys), d), dtype=torch.float64, device=device)
     dV = torch.zeros_like(dK)
     pairs = 0
@@ -84,10 +85,10 @@ def key_gradients(parent, seg_len, q, k, v, do, scale, keys, device="cpu", max_r
         n_own = int(seg_len[w])
         n_anc = len(ctx) - n_own
         # which context columns are requested keys, and where their sums go
-        cols = [j for j, tok in enumerate(ctx) if int(tok) in slot_of_key]
-        if not cols:
+        cols = np.flatnonzero(slot_of_token[ctx] >= 0)
+        if len(cols) == 0:
             continue
-        slots = torch.as_tensor([slot_of_key[int(ctx[j])] for j in cols], device=device)
+        slots = torch.as_tensor(slot_of_token[ctx[cols]], device=device)
         cols_t = torch.as_tensor(cols, device=device)
         ctx_t = torch.as_tensor(ctx, device=device)
         k_ctx, v_ctx = k[ctx_t], v[ctx_t]

@@ -151,6 +151,8 @@ class Tree:
     def __init__(self, handle, n_nodes):
         self._h = handle
         self.n_nodes = n_nodes
+        # the C ABI takes no tensor sizes: the wrappers compare every tensor with this
+        self.n_tokens = self.info()["n_tokens"]
 
     @property
     def handle(self):
@@ -224,6 +226,20 @@ def _stream():
     return C.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
+def _check_tree_tokens(tree, q):
+    """The kernels index rows 0 .. n_tokens-1 of every tensor, so tensors of another
+    tree (or a stale handle) must be refused here, before any launch."""
+    if tree.handle is None or not tree.handle:
+        raise ValueError("the tree has been destroyed")
+    if q.shape[0] != tree.n_tokens:
+        raise ValueError(f"tensors have {q.shape[0]} token rows, the tree has n_tokens = {tree.n_tokens}")
+
+
+def _check_workspace(workspace):
+    if workspace is not None and workspace.numel() and not (workspace.is_cuda and workspace.is_contiguous()):
+        raise ValueError("workspace must be a contiguous CUDA tensor")
+
+
 def _check_tensor(t, name, shape, dtype):
     if not t.is_cuda or not t.is_contiguous():
         raise ValueError(f"{name} must be a contiguous CUDA tensor")
@@ -235,6 +251,7 @@ def tree_attn_fwd(tree: Tree, params: AttnParams, q, k, v, o=None, lse=None, wor
     """dta_tree_attn_fwd on torch's current stream.  Returns (o, lse)."""
     import torch
     dt = torch.float32 if params.dtype == F32 else torch.bfloat16
+    _check_tree_tokens(tree, q)
     T = q.shape[0]
     _check_tensor(q, "q", (T, params.n_q_heads, params.head_dim), dt)
     _check_tensor(k, "k", (T, params.n_kv_heads, params.head_dim), dt)
@@ -249,6 +266,7 @@ def tree_attn_fwd(tree: Tree, params: AttnParams, q, k, v, o=None, lse=None, wor
         need = workspace_bytes(tree, params, False)
         if need:
             workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    _check_workspace(workspace)
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     st = load_library().dta_tree_attn_fwd(tree.handle, C.byref(params), _ptr(q), _ptr(k), _ptr(v),
                                           _ptr(o), _ptr(lse), _ptr(workspace), ws_bytes, _stream())
@@ -265,6 +283,7 @@ def tree_attn_bwd(tree: Tree, params: AttnParams, q, k, v, o, lse, d_o, dq=None,
     subset) on torch's current stream.  Returns (dq, dk, dv)."""
     import torch
     dt = torch.float32 if params.dtype == F32 else torch.bfloat16
+    _check_tree_tokens(tree, q)
     T = q.shape[0]
     _check_tensor(q, "q", (T, params.n_q_heads, params.head_dim), dt)
     _check_tensor(k, "k", (T, params.n_kv_heads, params.head_dim), dt)
@@ -281,6 +300,7 @@ def tree_attn_bwd(tree: Tree, params: AttnParams, q, k, v, o, lse, d_o, dq=None,
     if workspace is None:
         need = workspace_bytes(tree, params, True)
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    _check_workspace(workspace)
     ws_bytes = workspace.numel() * workspace.element_size()
     lib = load_library()
     args = (tree.handle, C.byref(params), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o),
@@ -297,6 +317,7 @@ def tree_attn_fwd_segment(tree: Tree, params: AttnParams, t_begin: int, t_end: i
     [t_begin, t_end) of the full-size o and lse."""
     import torch
     dt = torch.float32 if params.dtype == F32 else torch.bfloat16
+    _check_tree_tokens(tree, q)
     T = q.shape[0]
     _check_tensor(q, "q", (T, params.n_q_heads, params.head_dim), dt)
     _check_tensor(k, "k", (T, params.n_kv_heads, params.head_dim), dt)
@@ -315,6 +336,7 @@ def tree_attn_bwd_segment(tree: Tree, params: AttnParams, t_begin: int, t_end: i
     [t_begin, t_end) of dq and adds into the fp32 accumulators dk_acc, dv_acc."""
     import torch
     dt = torch.float32 if params.dtype == F32 else torch.bfloat16
+    _check_tree_tokens(tree, q)
     T = q.shape[0]
     _check_tensor(q, "q", (T, params.n_q_heads, params.head_dim), dt)
     _check_tensor(k, "k", (T, params.n_kv_heads, params.head_dim), dt)
@@ -325,6 +347,7 @@ def tree_attn_bwd_segment(tree: Tree, params: AttnParams, t_begin: int, t_end: i
     _check_tensor(dq, "dq", q.shape, dt)
     _check_tensor(dk_acc, "dk_acc", k.shape, torch.float32)
     _check_tensor(dv_acc, "dv_acc", v.shape, torch.float32)
+    _check_workspace(workspace)
     ws_bytes = workspace.numel() * workspace.element_size()
     st = load_library().dta_tree_attn_bwd_segment(tree.handle, C.byref(params), int(t_begin), int(t_end),
                                                   _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o),

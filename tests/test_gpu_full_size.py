@@ -7,6 +7,11 @@ here, so it is run on sampled outputs it can compute one by one:
   * dK, dV rows of a sampled subtree's nodes: every query that sees those keys
     lies inside the subtree, so the oracle restricted to the subtree's queries is
     complete for them;
+  * dK, dV of sampled SHARED-PREFIX keys (first tiles of the largest root, whose
+    walks are the ones the schedule splits into partial sums; the boundary between
+    a root and its first child; other roots of a forest; an interior node) against
+    every descendant query, with the per-key oracle;
+  * configuration 2: whole tensors, all five outputs, for one kv group;
 and on properties that hold at any size:
   * sum_k dV[k, g] == sum over the group's q heads and all tokens of dO (rows of P
     sum to one), per kv head and feature;
@@ -20,6 +25,7 @@ import pytest
 import torch
 
 import paper_2602_00482_amd as dta
+from oracle import key_gradient as K
 from oracle import tree_direct as B
 from oracle import tree_layout as L
 from workloads import config_heads, config_tree
@@ -211,3 +217,91 @@ def test_forward_without_workspace_gives_the_same_bits():
     torch.cuda.synchronize()
     tree.destroy()
     assert torch.equal(o1, o2) and torch.equal(l1, l2)
+
+
+def test_config2_whole_tensors_for_one_kv_group():
+    """Every row of O, LSE, dQ, dK, dV of one kv group (its four q heads) at the
+    benchmark size, against the tree-direct fp64 oracle on the CPU."""
+    parent, seg, (Hq, Hkv, d, scale), t = _run(2)
+    G = Hq // Hkv
+    grp = 5
+    hs = slice(grp * G, (grp + 1) * G)
+    host = lambda x: x.double().cpu().numpy()
+    q, do = host(t["q"][:, hs]), host(t["do"][:, hs])
+    k, v = host(t["k"][:, grp:grp + 1]), host(t["v"][:, grp:grp + 1])
+    O, LSE = B.forward(parent, seg, q, k, v, scale)
+    dQ, dK, dV = B.backward(parent, seg, q, k, v, do, scale)
+    errs = dict(o=_rel(host(t["o"][:, hs]), O), lse=_rel(host(t["lse"][:, hs]), LSE),
+                dq=_rel(host(t["dq"][:, hs]), dQ), dk=_rel(host(t["dk"][:, grp:grp + 1]), dK),
+                dv=_rel(host(t["dv"][:, grp:grp + 1]), dV))
+    print("cfg2 whole tensors, kv group 5: " + " ".join(f"{n}={e:.2e}" for n, e in errs.items()), flush=True)
+    assert all(e <= TOL for e in errs.values()), errs
+
+
+def _shared_prefix_keys(parent, seg, rng):
+    """Packed key indices whose gradients collect many descendants: the first 168
+    keys of the root with the largest subtree (two key tiles of the dK/dV
+    schedule, the longest walks of the launch), 96 keys across the end of that
+    root's segment and the start of its first child, 64 keys from the middle of
+    the root, the first 40 keys of up to three other roots, and 64 keys of a
+    random interior node."""
+    off, T = L.node_offsets(parent, seg)
+    _, kids = L.children_lists(parent)
+    sub = {}
+    for u in reversed(L.preorder(parent)):
+        sub[u] = int(seg[u]) + sum(sub[c] for c in kids[u])
+    roots = [u for u in range(len(parent)) if parent[u] < 0]
+    big = max(roots, key=lambda u: sub[u])
+    r0, r1 = int(off[big]), int(off[big]) + int(seg[big])
+    keys = set(range(r0, min(r1, r0 + 168)))
+    keys.update(range(max(r0, r1 - 48), min(T, r1 + 48)))
+    mid = (r0 + r1) // 2
+    keys.update(range(mid, min(r1, mid + 64)))
+    for u in [x for x in roots if x != big][:3]:
+        keys.update(range(int(off[u]), int(off[u]) + min(40, int(seg[u]))))
+    interior = [u for u in range(len(parent)) if kids[u] and parent[u] >= 0]
+    if interior:
+        u = int(rng.choice(interior))
+        keys.update(range(int(off[u]), int(off[u]) + min(64, int(seg[u]))))
+    return np.array(sorted(keys), dtype=np.int64)
+
+
+@pytest.mark.parametrize("cfg", [2, 3, 4, 5])
+def test_full_size_shared_prefix_key_gradients(cfg):
+    """dK and dV of shared-prefix keys, element by element, against the per-key
+    oracle summed over EVERY query that sees them (for a root key: all tokens of
+    its tree, for the four or eight q heads of the group).  The oracle's torch
+    lines run in fp64 on the GPU here (its matrix products go to the vendor
+    BLAS): at configuration 4 they are 10^13 floating-point operations; the same
+    lines are tied to the CPU evaluation below and in the CPU pins."""
+    parent, seg, (Hq, Hkv, d, scale), t = _run(cfg)
+    G = Hq // Hkv
+    rng = np.random.default_rng(40 + cfg)
+    grp = int(rng.integers(0, Hkv))
+    hs = slice(grp * G, (grp + 1) * G)
+    keys = _shared_prefix_keys(parent, seg, rng)
+    dK, dV, pairs = K.key_gradients(parent, seg, t["q"][:, hs], t["k"][:, grp], t["v"][:, grp], t["do"][:, hs],
+                                    scale, keys, device="cuda", max_rows=2048)
+    idx = torch.from_numpy(keys).cuda()
+    got_dk = t["dk"][idx, grp].double().cpu().numpy()
+    got_dv = t["dv"][idx, grp].double().cpu().numpy()
+    ek, ev = _rel(got_dk, dK), _rel(got_dv, dV)
+    print(f"cfg{cfg} kv group {grp}: {len(keys)} shared-prefix keys, oracle evaluated {pairs:.3e} (query row, "
+          f"visible key) pairs per q head: dk={ek:.2e} dv={ev:.2e}", flush=True)
+    assert ek <= TOL and ev <= TOL
+
+
+def test_per_key_oracle_gives_the_same_values_on_the_cpu_and_on_the_gpu():
+    """Ties the fp64 evaluation on the GPU used above to the CPU one (same lines,
+    other BLAS), on a scaled-down sibling of configuration 3."""
+    from workloads import make_inputs_numpy, scaled_config_tree
+    parent, seg, _ = scaled_config_tree(3, 16)
+    T = int(seg.sum())
+    x = make_inputs_numpy(T, 4, 1, 64, seed=77, dtype="bf16")
+    keys = _shared_prefix_keys(parent, seg, np.random.default_rng(3))
+    a = K.key_gradients(parent, seg, x["q"], x["k"][:, 0], x["v"][:, 0], x["do"], 0.125, keys)
+    b = K.key_gradients(parent, seg, x["q"], x["k"][:, 0], x["v"][:, 0], x["do"], 0.125, keys, device="cuda",
+                        max_rows=100)
+    assert a[2] == b[2]
+    for u, w in zip(a[:2], b[:2]):
+        assert np.abs(u - w).max() <= 1e-11 * max(1.0, np.abs(u).max())

@@ -183,3 +183,29 @@ def test_unary_chain_packs_like_one_segment():
     assert lay["anc_seg_off"][lay["anc_ptr"][2]:lay["anc_ptr"][3]].tolist() == [0]
     assert lay["anc_seg_len"][lay["anc_ptr"][2]:lay["anc_ptr"][3]].tolist() == [4]
     tree.destroy()
+
+
+def test_binding_refuses_tensors_of_another_tree_before_any_launch():
+    """The C ABI takes no tensor sizes, so a tree built for more tokens than the
+    tensors hold would make the kernels index past them.  The wrappers compare
+    the row count with the tree's n_tokens first (no GPU is needed to get the
+    refusal: CPU tensors of the wrong length are turned away for their length)."""
+    import torch
+    tree = dta.tree_build([-1, 0], [3, 4])
+    assert tree.n_tokens == 7
+    p = dta.AttnParams(2, 1, 128, 1.0, dta.BF16)
+    mk = lambda rows, heads, dt=torch.bfloat16: torch.zeros((rows, heads, 128), dtype=dt)
+    q, k, v = mk(5, 2), mk(5, 1), mk(5, 1)
+    lse = torch.zeros((5, 2))
+    with pytest.raises(ValueError, match="n_tokens = 7"):
+        dta.tree_attn_fwd(tree, p, q, k, v)
+    with pytest.raises(ValueError, match="n_tokens = 7"):
+        dta.tree_attn_bwd(tree, p, q, k, v, q, lse, q)
+    with pytest.raises(ValueError, match="n_tokens = 7"):
+        dta.tree_attn_fwd_segment(tree, p, 0, 3, q, k, v, q, lse)
+    with pytest.raises(ValueError, match="n_tokens = 7"):
+        dta.tree_attn_bwd_segment(tree, p, 0, 3, q, k, v, q, lse, q, q, mk(5, 1, torch.float32),
+                                  mk(5, 1, torch.float32), torch.zeros(256, dtype=torch.uint8))
+    tree.destroy()
+    with pytest.raises(ValueError, match="destroyed"):
+        dta.tree_attn_fwd(tree, p, mk(7, 2), mk(7, 1), mk(7, 1))
