@@ -39,17 +39,27 @@ WORKLOAD_NAMES = {
     8: "cfg8_low_compression_16k_answers",
 }
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
-# flop per unique pair per q head, in units of head_dim, that each launch must do
+# Matrix products each launch ISSUES per unique pair and q head, in units of head_dim.  The
+# forward's 4d are also its algorithmic work; the two backward launches issue 6d + 8d = 14d
+# for an algorithmic 10d, because the scores and dP are recomputed in both.
 KERNEL_FLOP_D = {"fwd": 4, "dq": 6, "dkdv": 8}
-# HBM bytes per launch (read + written) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
-# these workloads (`bench.py --traffic-probe --config N`), each counter scaled by what it reads
-# for the plain 1 GiB copy at the end of the probe (FETCH_SIZE x2.000, WRITE_SIZE x1.000); see
-# profiles/*_hbm_traffic.md.  Not measured live.  "dkdv" is the dK/dV stage as timed here:
-# the dK/dV kernel plus the reduction of split tiles.
-MEASURED_TRAFFIC_BYTES = {
-    "cfg2_grpo_single_prompt_tree": {"fwd": 4.58e8, "dq": 1.00e9, "dkdv": 3.21e9},
-    "cfg4_deep_long_context_tree": {"fwd": 6.36e10, "dq": 6.18e10, "dkdv": 4.22e11},
-}
+ALGORITHMIC_FLOP_D = {"fwd": 4, "bwd": 10}
+
+
+def committed_traffic_bytes(workload):
+    """HBM-side bytes per launch (read + written past the L2) of each kernel on this
+    workload, from the committed rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary
+    profiles/<workload>_hbm_traffic.md (line `traffic_bytes_per_launch: fwd=.. dq=.. dkdv=..`).
+    Counters cannot be read from inside a timed run, so this is not measured live; None
+    when there is no summary for the workload."""
+    import re
+    path = os.path.join(ROOT, "profiles", f"{workload}_hbm_traffic.md")
+    try:
+        text = open(path).read()
+    except OSError:
+        return None
+    m = re.search(r"traffic_bytes_per_launch:\s*fwd=(\S+)\s+dq=(\S+)\s+dkdv=(\S+)", text)
+    return None if m is None else {"fwd": float(m.group(1)), "dq": float(m.group(2)), "dkdv": float(m.group(3))}
 
 
 def _device_inputs(T, Hq, Hkv, d, seed, dtype):
@@ -340,11 +350,16 @@ def mfma_valu_overlap():
             "hidden_frac_of_shorter": (tm + tv - tb) / min(tm, tv), "both_over_sum": tb / (tm + tv)}
 
 
-def cpu_oracle_baseline(parent, seg, heads, seed, useful_flop):
-    """Oracle A (dense per-rollout, fp64 numpy) on a few kv groups of the workload
-    (about 10-15 s of CPU work), timed on this machine's host cores and extrapolated
-    linearly to all kv groups."""
+def cpu_oracle_baseline(parent, seg, heads, seed, useful_flop, budget_pairs=2.2e8):
+    """Oracle A (dense per-rollout, fp64 numpy, as it stands) on a bounded sample of the
+    workload, timed on this machine's host cores: whole rollouts (longest first), the q heads
+    of one kv group, as many (rollout, q head) pairs as fit a budget of dense score
+    entries (about 10-30 s of CPU work).  Every rollout of the sample is handed to the
+    oracle as the single-chain tree of its root path, which is what the oracle expands
+    the tree into anyway.  The whole job is every rollout x every q head; the measured
+    time is extrapolated linearly by dense causal pairs and labelled as such."""
     from oracle import dense_rollout as A
+    from oracle import tree_layout as L
     from workloads import make_inputs_numpy
     try:
         from threadpoolctl import threadpool_info
@@ -353,21 +368,39 @@ def cpu_oracle_baseline(parent, seg, heads, seed, useful_flop):
         threads = os.cpu_count()
     Hq, Hkv, d = heads["n_q_heads"], heads["n_kv_heads"], heads["head_dim"]
     G = Hq // Hkv
-    T = int(np.sum(seg))
-    n_groups = min(Hkv, 3)
-    x = make_inputs_numpy(T, G * n_groups, n_groups, d, seed, dtype=heads["dtype"])
     scale = 1.0 / math.sqrt(d)
-    t0 = time.perf_counter()
-    A.forward(parent, seg, x["q"], x["k"], x["v"], scale)
-    A.backward(parent, seg, x["q"], x["k"], x["v"], x["do"], scale)
-    dt = time.perf_counter() - t0
-    full = dt * Hkv / n_groups
+    sd = L.start_depths(parent, seg)
+    leaves = sorted(L.leaves(parent), key=lambda u: -(int(sd[u]) + int(seg[u])))
+    dense_pairs_job = sum((int(sd[u]) + int(seg[u])) * (int(sd[u]) + int(seg[u]) + 1) // 2 for u in leaves) * Hq
+    sample, pairs = [], 0
+    for u in leaves:                                   # (leaf, number of q heads of the group)
+        n = int(sd[u]) + int(seg[u])
+        per_head = n * (n + 1) // 2
+        nh = int(min(G, max(0, (budget_pairs - pairs) // per_head)))
+        if nh == 0 and not sample:
+            nh = 1                                     # at least one (rollout, head), whatever its size
+        if nh == 0:
+            break
+        sample.append((u, nh))
+        pairs += nh * per_head
+    dt = 0.0
+    for i, (u, nh) in enumerate(sample):
+        path = L.node_path(parent, u)
+        chain_parent = np.arange(-1, len(path) - 1, dtype=np.int32)
+        chain_seg = np.asarray([seg[a] for a in path], dtype=np.int32)
+        x = make_inputs_numpy(int(chain_seg.sum()), nh, 1, d, seed + i, dtype=heads["dtype"])
+        t0 = time.perf_counter()
+        A.forward(chain_parent, chain_seg, x["q"], x["k"], x["v"], scale)
+        A.backward(chain_parent, chain_seg, x["q"], x["k"], x["v"], x["do"], scale)
+        dt += time.perf_counter() - t0
+    full = dt * dense_pairs_job / pairs
     return {"value": useful_flop / full / 1e12, "unit": "TFLOP/s", "cores": int(threads),
             "kind": "oracle",
-            "sample": f"dense per-rollout fp64 oracle, fwd+bwd, {n_groups} of {Hkv} kv groups ({G * n_groups} q heads), "
-                      f"all rollouts: {dt:.1f} s measured, x{Hkv}/{n_groups} extrapolated to {full:.0f} s for the "
-                      f"whole job",
-            "seconds_measured": dt}
+            "sample": f"dense per-rollout fp64 oracle, fwd+bwd, {len(sample)} of {len(leaves)} rollouts (longest first) "
+                      f"x {'/'.join(str(nh) for _, nh in sample)} of {Hq} q heads = {pairs:.3e} dense causal pairs: "
+                      f"{dt:.1f} s measured; the whole job is {dense_pairs_job:.3e} dense pairs, extrapolated "
+                      f"linearly to {full:.0f} s; value = the job's unique-pair flop / that time",
+            "seconds_measured": dt, "seconds_extrapolated": full}
 
 
 def main():
@@ -375,8 +408,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 2..8 of the main line")
-    ap.add_argument("--others", type=str, default="3,4,5,6,7,8", help="configs reported as extra objects ('' = none)")
+    ap.add_argument("--config", type=int, default=4,
+                    help="benchmark configuration 2..8 of the main line (default: 4, the largest single-GPU one)")
+    ap.add_argument("--others", type=str, default="2,3,5,6,7,8", help="configs reported as extra objects ('' = none)")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-segments", action="store_true",
@@ -448,8 +482,13 @@ def main():
             "kernel_ms": {k: round(v, 4) for k, v in kern.items()},
             "kernel_ms_min": {k: round(v, 4) for k, v in r.kernel_ms_min.items()},
             "host": dict(r.time_tree_build(), metadata_bytes=sched["metadata_bytes"]),
-            "kernel_tflops": {k: pairs * Hq * KERNEL_FLOP_D[k] * d / (kern[k] * 1e-3) / 1e12
-                              for k in KERNEL_FLOP_D},
+            # per launch, on the products that launch issues (fwd 4d, dq 6d, dkdv 8d) ...
+            "kernel_tflops_issued": {k: pairs * Hq * KERNEL_FLOP_D[k] * d / (kern[k] * 1e-3) / 1e12
+                                     for k in KERNEL_FLOP_D},
+            # ... and on algorithmic work: forward 4d, the two backward launches together 10d
+            "kernel_tflops_algorithmic": {
+                "fwd": pairs * Hq * 4 * d / (kern["fwd"] * 1e-3) / 1e12,
+                "bwd": pairs * Hq * 10 * d / ((kern["dq"] + kern["dkdv"]) * 1e-3) / 1e12},
             "schedule": sched,
             "C_leaf": info["rollout_tokens"] / info["n_tokens"],
             "C_full": info["rollout_tokens_full"] / info["n_tokens"],
@@ -482,11 +521,22 @@ def main():
     main_res, kern, info, heads, cpu = measure(args.config, args.steps, args.warmup,
                                                not args.no_dense, not args.no_cpu, not args.no_segments)
     Hq, d = heads["n_q_heads"], heads["head_dim"]
-    dom = max(KERNEL_FLOP_D, key=lambda k: kern[k])
-    achieved = info["unique_pairs"] * Hq * KERNEL_FLOP_D[dom] * d / (kern[dom] * 1e-3) / 1e12
     peak = PEAK_TFLOPS[heads["dtype"]]
+    pairs_h = info["unique_pairs"] * Hq
+    # The dominant launches are the backward's two (dQ, then dK/dV with the reduction of split
+    # tiles), which together do the algorithmic 10d per pair and q head; the roofline is
+    # priced on that, with each launch's duration (HIP events on the launch stream) and the
+    # rate on the products it issues beside it.
+    bwd_ms = kern["dq"] + kern["dkdv"]
+    achieved = pairs_h * ALGORITHMIC_FLOP_D["bwd"] * d / (bwd_ms * 1e-3) / 1e12
+    traffic = committed_traffic_bytes(main_res["workload"])
     sustained = mfma_sustained_rate()
     overlap = mfma_valu_overlap()
+    per_kernel = {k: {"avg_launch_ms": kern[k], "issued_flop_per_pair_per_head": KERNEL_FLOP_D[k] * d,
+                      "issued_tflops": pairs_h * KERNEL_FLOP_D[k] * d / (kern[k] * 1e-3) / 1e12,
+                      "issued_frac_of_peak": pairs_h * KERNEL_FLOP_D[k] * d / (kern[k] * 1e-3) / 1e12 / peak,
+                      "traffic": None if traffic is None else traffic[k]} for k in KERNEL_FLOP_D}
+    per_kernel["fwd"]["algorithmic_tflops"] = per_kernel["fwd"]["issued_tflops"]
     line = {
         "metric": "tree_attn_fwd_bwd_unique_pair_tflops", "value": main_res["useful_tflops"],
         "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -494,10 +544,12 @@ def main():
         "vs_baseline": None, "dtype": heads["dtype"], "data": "synthetic",
         "config": {k: main_res[k] for k in ("workload", "n_tokens", "n_nodes", "n_leaves", "max_path_tokens",
                                             "unique_pairs", "heads", "head_dim", "tree_seed", "tensor_seed")},
-        "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                     "frac": achieved / peak,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(main_res["workload"], {}).get(dom),
-                     "flop_per_pair_per_head": KERNEL_FLOP_D[dom] * d, "avg_launch_ms": kern[dom],
+        "roofline": {"bound": "mfma", "kernel": "bwd (dq launch + dkdv launch)", "achieved": achieved, "peak": peak,
+                     "unit": "TFLOP/s", "frac": achieved / peak,
+                     "traffic": None if traffic is None else traffic["dq"] + traffic["dkdv"],
+                     "flop_per_pair_per_head": ALGORITHMIC_FLOP_D["bwd"] * d, "avg_launch_ms": bwd_ms,
+                     "per_kernel": per_kernel,
+                     "whole_step_frac": main_res["mfma_frac_of_peak"],
                      # what this GPU's matrix pipes sustain on products alone (measured just now),
                      # beside the published peak that `frac` is priced against
                      "mfma_only_probe": sustained, "frac_of_probe": achieved / sustained["tflops"],
