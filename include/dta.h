@@ -212,6 +212,31 @@ int dta_tree_attn_bwd_stages(dta_tree_t* tree, const dta_attn_params_t* params, 
                              size_t workspace_bytes, void* hip_stream, uint32_t stage_mask);
 
 /*
+ * dta_tree_attn_bwd_noalloc - dta_tree_attn_bwd for callers that cannot allocate
+ * device memory: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments, results and bits as dta_tree_attn_bwd,
+ * without the workspace: the scratch memory (row statistics, work-queue
+ * counters, fp32 partial sums of split key tiles) is a device array of 160 MiB
+ * that the library holds on every GPU it runs on until the process ends.  The
+ * call allocates and frees nothing, on the host side of HIP or on the device:
+ *  - the tree's device metadata for this head configuration must already be
+ *    resident on the current device (dta_tree_attn_prepare, which may
+ *    allocate, also resolves the scratch array's address on that device), else
+ *    DTA_ERR_INVALID_ARG;
+ *  - DTA_ERR_WORKSPACE, with a message on stderr, when
+ *    dta_tree_attn_workspace_bytes(tree, params, 1) exceeds 160 MiB (the
+ *    benchmark configurations need 35 to 130 MiB);
+ *  - every call on a GPU uses that GPU's one array, which keeps the previous
+ *    call's contents: nothing in it needs to start from zero except the queue
+ *    counters, which the call clears itself with a fill kernel, and calls that
+ *    overlap in time on one GPU (two streams, two threads) race on it.  Order
+ *    them on one stream or with events.
+ */
+int dta_tree_attn_bwd_noalloc(dta_tree_t* tree, const dta_attn_params_t* params, const void* q,
+                              const void* k, const void* v, const void* o, const float* lse,
+                              const void* d_o, void* dq, void* dk, void* dv, void* hip_stream);
+
+/*
  * Segment calls: the attention inside the paper's FWD(l_start -> l_end) and BWD
  * primitives (pseudocode appendix, notation block), which its push / pop
  * traversal issues once per token segment (section 3.1; vanilla algorithm), and

@@ -19,7 +19,7 @@ F32, BF16 = 0, 1
 exported_symbols = [
     "dta_tree_build", "dta_tree_info", "dta_tree_layout", "dta_tree_schedule_info",
     "dta_tree_destroy", "dta_tree_attn_workspace_bytes", "dta_tree_attn_prepare",
-    "dta_tree_attn_fwd", "dta_tree_attn_bwd", "dta_tree_attn_bwd_stages",
+    "dta_tree_attn_fwd", "dta_tree_attn_bwd", "dta_tree_attn_bwd_stages", "dta_tree_attn_bwd_noalloc",
     "dta_tree_attn_fwd_segment", "dta_tree_attn_bwd_segment", "dta_rollouts_build",
     "dta_rollouts_view", "dta_rollouts_destroy", "dta_rollouts_partition", "dta_tree_plan",
     "dta_plan_view", "dta_plan_destroy", "dta_probe_mfma_bf16", "dta_probe_overlap", "dta_status_string",
@@ -109,6 +109,8 @@ def load_library():
     lib.dta_tree_attn_bwd.restype = C.c_int
     lib.dta_tree_attn_bwd_stages.argtypes = [vp, C.POINTER(AttnParams)] + [vp] * 9 + [vp, C.c_size_t, vp, C.c_uint32]
     lib.dta_tree_attn_bwd_stages.restype = C.c_int
+    lib.dta_tree_attn_bwd_noalloc.argtypes = [vp, C.POINTER(AttnParams)] + [vp] * 9 + [vp]
+    lib.dta_tree_attn_bwd_noalloc.restype = C.c_int
     lib.dta_tree_attn_fwd_segment.argtypes = ([vp, C.POINTER(AttnParams), C.c_int64, C.c_int64] + [vp] * 5 +
                                               [vp, C.c_size_t, vp])
     lib.dta_tree_attn_fwd_segment.restype = C.c_int
@@ -310,6 +312,26 @@ def tree_attn_bwd(tree: Tree, params: AttnParams, q, k, v, o, lse, d_o, dq=None,
     else:
         _check(lib.dta_tree_attn_bwd_stages(*args, int(stages)), "dta_tree_attn_bwd_stages")
     return dq, dk, dv
+
+
+def tree_attn_bwd_noalloc(tree: Tree, params: AttnParams, q, k, v, o, lse, d_o, dq, dk, dv):
+    """dta_tree_attn_bwd_noalloc on torch's current stream: the backward pass on
+    the library-held scratch array; every tensor, outputs included, is the
+    caller's, and the tree must have been prepared (Tree.prepare)."""
+    import torch
+    dt = torch.float32 if params.dtype == F32 else torch.bfloat16
+    _check_tree_tokens(tree, q)
+    T = q.shape[0]
+    for name, t, heads in (("q", q, params.n_q_heads), ("k", k, params.n_kv_heads), ("v", v, params.n_kv_heads),
+                           ("o", o, params.n_q_heads), ("d_o", d_o, params.n_q_heads),
+                           ("dq", dq, params.n_q_heads), ("dk", dk, params.n_kv_heads),
+                           ("dv", dv, params.n_kv_heads)):
+        _check_tensor(t, name, (T, heads, params.head_dim), dt)
+    _check_tensor(lse, "lse", (T, params.n_q_heads), torch.float32)
+    st = load_library().dta_tree_attn_bwd_noalloc(tree.handle, C.byref(params), _ptr(q), _ptr(k), _ptr(v),
+                                                  _ptr(o), _ptr(lse), _ptr(d_o), _ptr(dq), _ptr(dk), _ptr(dv),
+                                                  _stream())
+    _check(st, "dta_tree_attn_bwd_noalloc")
 
 
 def tree_attn_fwd_segment(tree: Tree, params: AttnParams, t_begin: int, t_end: int, q, k, v, o, lse):

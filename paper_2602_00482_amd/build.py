@@ -10,7 +10,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libdta.so")
-SOURCES = ["dta_tree.cpp", "dta_rollouts.cpp", "dta_plan.cpp", "dta_api.hip", "dta_f32_kernels.hip", "dta_bf16_fwd.hip", "dta_bf16_bwd.hip", "dta_probe.hip"]
+SOURCES = ["dta_tree.cpp", "dta_rollouts.cpp", "dta_plan.cpp", "dta_api.hip", "dta_f32_kernels.hip", "dta_bf16_fwd.hip", "dta_bf16_bwd.hip", "dta_noalloc.hip", "dta_probe.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",
@@ -43,10 +43,25 @@ def build(verbose: bool = False) -> str:
     return LIB_PATH
 
 
+def _stale() -> bool:
+    """True when a source or header is newer than the built library (work-list
+    records are shared between separately compiled host and device objects, so a
+    half-rebuilt or outdated library must never be loaded)."""
+    built = os.path.getmtime(LIB_PATH)
+    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hip", ".cpp", ".h"))]
+    deps.append(os.path.join(ROOT, "include", "dta.h"))
+    return any(os.path.getmtime(d) > built for d in deps)
+
+
 def ensure_built() -> str:
-    """Build only if no library is there (tests, the smoke run and the benchmark
-    call this; whoever changes a source builds explicitly)."""
-    return LIB_PATH if os.path.exists(LIB_PATH) else build()
+    """Build if no library is there or a source is newer than it (tests, the smoke
+    run and the benchmark call this).  On a machine without the compiler a library
+    that is there is used as it is."""
+    if not os.path.exists(LIB_PATH):
+        return build()
+    if _stale() and os.path.exists(HIPCC):
+        return build()
+    return LIB_PATH
 
 
 if __name__ == "__main__":

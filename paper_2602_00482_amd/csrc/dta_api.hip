@@ -195,13 +195,25 @@ Part part_of(const std::vector<T>& v, T** dst) {
 // device.  Takes the tree lock; blocking (on the upload only) on first use, a
 // no-op afterwards.
 int ensure_device(dta_tree* tree, const dta::TileChoice& tc, const dta_attn_params_t* p,
-                  dta::Schedule** out, int64_t t_begin = -1, int64_t t_end = -1) {
+                  dta::Schedule** out, int64_t t_begin = -1, int64_t t_end = -1,
+                  bool allocate_ok = true) {
   std::lock_guard<std::mutex> lock(tree->mu);
   int dev = -1;
   if (hipGetDevice(&dev) != hipSuccess) {
     fprintf(stderr, "dta: hipGetDevice failed (no usable GPU?)\n");
     (void)hipGetLastError();
     return DTA_ERR_HIP;
+  }
+  if (!allocate_ok) {
+    // a caller that must not allocate: everything has to be resident already
+    // (dta_tree_attn_prepare on this device); look, do not build
+    const uint64_t key = dta::schedule_key(tc.bm, tc.bn, p->n_kv_heads, p->n_q_heads / p->n_kv_heads);
+    auto it = tree->schedules.find(key);
+    if (it == tree->schedules.end() || it->second.device != dev || tree->kend_device != dev ||
+        !tree->last_use)
+      return DTA_ERR_INVALID_ARG;
+    *out = &it->second;
+    return DTA_OK;
   }
   dta::Schedule* s;
   try {
@@ -316,7 +328,14 @@ int dta_tree_attn_prepare(dta_tree_t* tree, const dta_attn_params_t* params) {
   int st = dta::choose_tiles(params, &tc);
   if (st != DTA_OK) return st;
   dta::Schedule* s = nullptr;
-  return ensure_device(tree, tc, params, &s);
+  if ((st = ensure_device(tree, tc, params, &s)) != DTA_OK) return st;
+  // set-up for dta_tree_attn_bwd_noalloc: resolve this device's copy of the
+  // library-held scratch array now, so that the call itself has nothing left to do
+  int dev = -1;
+  void* scratch = nullptr;
+  size_t scratch_bytes = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return DTA_ERR_HIP;
+  return dta::static_scratch(dev, &scratch, &scratch_bytes);
 }
 
 int dta_tree_attn_fwd(dta_tree_t* tree, const dta_attn_params_t* params, const void* q,
@@ -358,6 +377,24 @@ int dta_tree_attn_bwd_stages(dta_tree_t* tree, const dta_attn_params_t* params, 
                              const void* k, const void* v, const void* o, const float* lse,
                              const void* d_o, void* dq, void* dk, void* dv, void* workspace,
                              size_t workspace_bytes, void* hip_stream, uint32_t stage_mask) {
+  return dta::bwd_entry(tree, params, q, k, v, o, lse, d_o, dq, dk, dv, workspace, workspace_bytes,
+                        hip_stream, stage_mask, true);
+}
+
+}  // extern "C"
+
+namespace dta {
+
+size_t bwd_workspace_need(dta_tree* tree, const dta_attn_params_t* params) {
+  TileChoice tc;
+  if (!tree || choose_tiles(params, &tc) != DTA_OK) return 0;
+  return bwd_workspace_bytes(tree, tc, params);
+}
+
+int bwd_entry(dta_tree* tree, const dta_attn_params_t* params, const void* q, const void* k,
+              const void* v, const void* o, const float* lse, const void* d_o, void* dq, void* dk,
+              void* dv, void* workspace, size_t workspace_bytes, void* hip_stream,
+              uint32_t stage_mask, bool allocate_ok) {
   if (!tree || !params) return DTA_ERR_INVALID_ARG;
   if (stage_mask == 0 || (stage_mask & ~(uint32_t)DTA_BWD_ALL)) return DTA_ERR_INVALID_ARG;
   dta::TileChoice tc;
@@ -373,7 +410,7 @@ int dta_tree_attn_bwd_stages(dta_tree_t* tree, const dta_attn_params_t* params, 
       ((uintptr_t)workspace & 255u))
     return DTA_ERR_WORKSPACE;
   dta::Schedule* s = nullptr;
-  if ((st = ensure_device(tree, tc, params, &s)) != DTA_OK) return st;
+  if ((st = ensure_device(tree, tc, params, &s, -1, -1, allocate_ok)) != DTA_OK) return st;
   dta::LaunchArgs a{};
   a.tree = tree;
   a.sched = s;
@@ -400,6 +437,10 @@ int dta_tree_attn_bwd_stages(dta_tree_t* tree, const dta_attn_params_t* params, 
   return mark_use(tree, hip_stream,
                   params->dtype == DTA_F32 ? dta::launch_bwd_f32(a) : dta::launch_bwd_bf16(a));
 }
+
+}  // namespace dta
+
+extern "C" {
 
 int dta_tree_attn_bwd(dta_tree_t* tree, const dta_attn_params_t* params, const void* q,
                       const void* k, const void* v, const void* o, const float* lse,

@@ -126,6 +126,10 @@ namespace dta {
 // 256 CUs of an MI355X times the blocks of that kernel that fit on a CU.
 constexpr int kNumCUs = 256;
 
+// Key of a whole-tree schedule in dta_tree::schedules.
+inline uint64_t schedule_key(int bm, int bn, int hkv, int group) {
+  return ((uint64_t)bm << 48) | ((uint64_t)bn << 32) | ((uint64_t)hkv << 16) | (uint64_t)group;
+}
 // Host: build (or fetch) the schedule for tile sizes (bm, bn).
 Schedule& get_schedule(dta_tree* tree, int bm, int bn, int hkv, int group);
 // Same for a segment call on rows [t_begin, t_end), which must lie inside one
@@ -174,6 +178,19 @@ struct LaunchArgs {
 // status and names a failure on stderr.
 void clear_hip_error();
 int launch_status(const char* what);
+
+// The backward entry points share this: argument checks, metadata residency and
+// launch.  allocate_ok = false refuses (DTA_ERR_INVALID_ARG) instead of building
+// or uploading anything that is not resident yet.
+int bwd_entry(dta_tree* tree, const dta_attn_params_t* params, const void* q, const void* k,
+              const void* v, const void* o, const float* lse, const void* d_o, void* dq, void* dk,
+              void* dv, void* workspace, size_t workspace_bytes, void* hip_stream,
+              uint32_t stage_mask, bool allocate_ok);
+// Backward workspace bytes for a tree whose schedule may still have to be built.
+size_t bwd_workspace_need(dta_tree* tree, const dta_attn_params_t* params);
+// Device address and size of the library-held scratch array on device `dev`,
+// which must be the current device (resolved once per device, then cached).
+int static_scratch(int dev, void** ptr, size_t* bytes);
 
 // Kernel launchers (defined in the .hip files); return a DTA status.
 int launch_fwd_f32(const LaunchArgs& a);

@@ -184,7 +184,7 @@ size_t partial_bytes(const Schedule& s) {
 }
 
 Schedule& get_schedule(dta_tree* tree, int bm, int bn, int hkv, int group) {
-  uint64_t key = ((uint64_t)bm << 48) | ((uint64_t)bn << 32) | ((uint64_t)hkv << 16) | (uint64_t)group;
+  const uint64_t key = schedule_key(bm, bn, hkv, group);
   auto it = tree->schedules.find(key);
   if (it != tree->schedules.end()) return it->second;
   Schedule& s = tree->schedules[key];
@@ -318,9 +318,8 @@ Schedule& get_schedule(dta_tree* tree, int bm, int bn, int hkv, int group) {
 
 Schedule& get_segment_schedule(dta_tree* tree, int bm, int bn, int hkv, int group,
                                int64_t t_begin, int64_t t_end) {
-  const std::array<uint64_t, 3> key = {
-      ((uint64_t)bm << 48) | ((uint64_t)bn << 32) | ((uint64_t)hkv << 16) | (uint64_t)group,
-      (uint64_t)t_begin, (uint64_t)t_end};
+  const std::array<uint64_t, 3> key = {schedule_key(bm, bn, hkv, group), (uint64_t)t_begin,
+                                       (uint64_t)t_end};
   auto it = tree->segment_schedules.find(key);
   if (it != tree->segment_schedules.end()) return it->second;
   Schedule& s = tree->segment_schedules[key];
