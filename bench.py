@@ -298,7 +298,7 @@ def mfma_sustained_rate():
     library's probe kernel: same instruction and block shape as the attention
     kernels, register operands), and the shader clock during that run."""
     import torch
-    import paper_2602_00482_amd as dta
+    from paper_2602_00482_amd import probe
     n_blocks, iters = 512, 20000          # two blocks on each of 256 CUs, about 10 ms
     out = torch.empty(n_blocks * 256, dtype=torch.float32, device="cuda")
     ticks = torch.zeros(2 * n_blocks, dtype=torch.int64, device="cuda")
@@ -306,7 +306,7 @@ def mfma_sustained_rate():
     best = None
     for rep in range(4):                  # first one warms up; the power state settles over the others
         ev[0].record()
-        flop, wall_khz = dta.probe_mfma_bf16(n_blocks, iters, out, ticks)
+        flop, wall_khz = probe.probe_mfma_bf16(n_blocks, iters, out, ticks)
         ev[1].record()
         torch.cuda.synchronize()
         ms = ev[0].elapsed_time(ev[1])
@@ -325,7 +325,7 @@ def mfma_valu_overlap():
     The attention kernels' time is products plus exponentials and their
     bookkeeping, so this bounds what any schedule of them can reach."""
     import torch
-    import paper_2602_00482_amd as dta
+    from paper_2602_00482_amd import probe
     n_blocks, iters = 256, 20000          # one block of 8 waves per CU
     out = torch.empty(n_blocks * 512, dtype=torch.float32, device="cuda")
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
@@ -334,7 +334,7 @@ def mfma_valu_overlap():
         best = None
         for _ in range(3):
             ev[0].record()
-            dta.probe_overlap(n_blocks, m, v, out)
+            probe.probe_overlap(n_blocks, m, v, out)
             ev[1].record()
             torch.cuda.synchronize()
             ms = ev[0].elapsed_time(ev[1])
@@ -350,7 +350,7 @@ def mfma_valu_overlap():
             "hidden_frac_of_shorter": (tm + tv - tb) / min(tm, tv), "both_over_sum": tb / (tm + tv)}
 
 
-def cpu_oracle_baseline(parent, seg, heads, seed, useful_flop, budget_pairs=2.2e8):
+def cpu_oracle_baseline(parent, seg, heads, seed, useful_flop, budget_pairs=8.5e8):
     """Oracle A (dense per-rollout, fp64 numpy, as it stands) on a bounded sample of the
     workload, timed on this machine's host cores: whole rollouts (longest first), the q heads
     of one kv group, as many (rollout, q head) pairs as fit a budget of dense score

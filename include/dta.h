@@ -121,7 +121,18 @@ int dta_tree_build(const int32_t* parent, const int32_t* seg_len, int32_t n_node
  * of the paper's figure 1, S = 1 - 1/C its prefix-sharing rate. */
 int dta_tree_info(const dta_tree_t* tree, dta_tree_info_t* out);
 
-/* Packed layout and per-node ancestor-segment lists (borrowed host pointers). */
+/*
+ * dta_tree_layout - where every node's tokens sit in the packed tensors, and which
+ * key intervals its queries see: the tree of token segments of the paper's
+ * problem formulation (section 3) laid out in one DFS order (any DFS order of the
+ * tree is valid, section 4).  A token of node u at in-node index j is row
+ * node_offset[u] + j and has position node_start_depth[u] + j on its root path
+ * (depth is counted in tokens, section 3.1, space complexity); its queries see
+ * the intervals anc_seg_*[anc_ptr[u] .. anc_ptr[u+1]) (the segments of u's
+ * ancestors, root first) and rows node_offset[u] .. node_offset[u] + j of u
+ * itself.  Host only; the pointers are borrowed and stay valid until
+ * dta_tree_destroy.
+ */
 int dta_tree_layout(const dta_tree_t* tree, dta_tree_layout_t* out);
 
 /* Builds (and caches in the tree) the DFS tile schedule for this head
@@ -166,6 +177,10 @@ int dta_tree_attn_prepare(dta_tree_t* tree, const dta_attn_params_t* params);
  *               queues, which is a few per cent slower on large inputs and gives
  *               the same bits
  *   hip_stream : a hipStream_t (NULL = default stream)
+ * The tree is not const: the first call for a head configuration builds and caches
+ * the tile schedule in it and, unless dta_tree_attn_prepare has done so, allocates
+ * device memory for the tree's metadata and waits for its upload (see the general
+ * rules above); later calls with the same configuration only enqueue.
  * bf16 mode multiplies in bf16 on the matrix cores and accumulates / does the
  * softmax in fp32; fp32 mode is fp32 throughout.
  */
@@ -187,6 +202,8 @@ int dta_tree_attn_fwd(dta_tree_t* tree, const dta_attn_params_t* params, const v
  *   dq : device [T,Hq,d] out;  dk, dv : device [T,Hkv,d] out.  All three are
  *        OVERWRITTEN (each element written exactly once, no atomics).
  *   workspace : device, >= dta_tree_attn_workspace_bytes(tree, params, 1)
+ * As for the forward, the first call for a head configuration may build the
+ * schedule and allocate / upload the tree's device metadata.
  */
 int dta_tree_attn_bwd(dta_tree_t* tree, const dta_attn_params_t* params, const void* q,
                       const void* k, const void* v, const void* o, const float* lse,
@@ -390,45 +407,6 @@ int dta_tree_plan(const dta_tree_t* tree, int64_t block, dta_plan_t** out);
 /* Borrowed host pointers into the plan, valid until dta_plan_destroy. */
 int dta_plan_view(const dta_plan_t* plan, dta_plan_view_t* out);
 void dta_plan_destroy(dta_plan_t* plan);
-
-/*
- * dta_probe_mfma_bf16 - measurement helper, not part of the method: enqueues a
- * kernel that does nothing but bf16 matrix-core products (the instruction and
- * block shape of the attention kernels, register operands, no memory traffic)
- * so that a caller who times it gets the rate the matrix pipes of this GPU
- * sustain under its power limit, the practical ceiling beside the published
- * peak that the roofline of the attention kernels is priced against.
- *
- * n_blocks blocks of 256 threads, `iters` iterations of 16 products per wave.
- * out   [n_blocks * 256] fp32, device: written (keeps the work observable).
- * ticks [2 * n_blocks] uint64, device: per block, the shader-clock cycles and
- *       the constant-rate wall-clock ticks the loop took; their ratio times
- *       the wall-clock rate gives the shader clock during the run.
- * *flop (host, may be NULL) receives the floating-point operations of the
- * launch: n_blocks * 4 waves * iters * 16 * (2*32*32*16).
- * *wall_clock_khz (host, may be NULL) receives the rate of the wall-clock
- * counter on the current device.
- * Asynchronous on hip_stream; allocates nothing.  INVALID_ARG for null buffers,
- * n_blocks outside [1, 2^20] or iters outside [1, 2^24].
- */
-int dta_probe_mfma_bf16(int32_t n_blocks, int32_t iters, float* out, uint64_t* ticks, void* hip_stream,
-                        int64_t* flop, int32_t* wall_clock_khz);
-
-/*
- * dta_probe_overlap - measurement helper, not part of the method: how much of
- * the vector-ALU work of one wave does the hardware hide behind the matrix
- * products of ANOTHER wave on the same SIMD?  Enqueues n_blocks blocks of 8
- * waves (two per SIMD): waves 0-3 do mfma_iters x 16 bf16 matrix products, waves
- * 4-7 do valu_iters x 64 v_exp_f32, all on registers.  The caller times three
- * launches (valu_iters = 0, mfma_iters = 0, both); `both` between max and sum of
- * the other two says how far any schedule of the attention kernels, whose time
- * is products plus exponentials, can go.
- * out [n_blocks * 512] fp32, device: written.  Asynchronous on hip_stream;
- * allocates nothing.  INVALID_ARG for a null buffer, n_blocks outside [1, 2^20]
- * or an iteration count outside [0, 2^24].
- */
-int dta_probe_overlap(int32_t n_blocks, int32_t mfma_iters, int32_t valu_iters, float* out,
-                      void* hip_stream);
 
 /* Static, human-readable name of a status code. */
 const char* dta_status_string(int status);

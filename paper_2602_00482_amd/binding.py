@@ -22,7 +22,7 @@ exported_symbols = [
     "dta_tree_attn_fwd", "dta_tree_attn_bwd", "dta_tree_attn_bwd_stages", "dta_tree_attn_bwd_noalloc",
     "dta_tree_attn_fwd_segment", "dta_tree_attn_bwd_segment", "dta_rollouts_build",
     "dta_rollouts_view", "dta_rollouts_destroy", "dta_rollouts_partition", "dta_tree_plan",
-    "dta_plan_view", "dta_plan_destroy", "dta_probe_mfma_bf16", "dta_probe_overlap", "dta_status_string",
+    "dta_plan_view", "dta_plan_destroy", "dta_status_string",
 ]
 
 
@@ -131,11 +131,6 @@ def load_library():
     lib.dta_plan_view.restype = C.c_int
     lib.dta_plan_destroy.argtypes = [vp]
     lib.dta_plan_destroy.restype = None
-    lib.dta_probe_mfma_bf16.argtypes = [C.c_int32, C.c_int32, vp, vp, vp, C.POINTER(C.c_int64),
-                                        C.POINTER(C.c_int32)]
-    lib.dta_probe_mfma_bf16.restype = C.c_int
-    lib.dta_probe_overlap.argtypes = [C.c_int32, C.c_int32, C.c_int32, vp, vp]
-    lib.dta_probe_overlap.restype = C.c_int
     lib.dta_status_string.argtypes = [C.c_int]
     lib.dta_status_string.restype = C.c_char_p
     _lib = lib
@@ -445,25 +440,3 @@ def tree_plan(tree: Tree, block: int = 0) -> dict:
             max_stack_tokens=int(v.max_stack_tokens))
     finally:
         lib.dta_plan_destroy(h)
-
-
-def probe_mfma_bf16(n_blocks: int, iters: int, out, ticks):
-    """dta_probe_mfma_bf16: enqueues the matrix-pipe rate probe; out is a device
-    fp32 tensor of n_blocks*256 elements, ticks a device int64 tensor of
-    2*n_blocks; runs on torch's current stream.  Returns (floating-point operations of the launch,
-    rate of the wall-clock counter in kHz)."""
-    if out.numel() < n_blocks * 256 or ticks.numel() < 2 * n_blocks or ticks.element_size() != 8:
-        raise ValueError("probe buffers too small")
-    flop, khz = C.c_int64(), C.c_int32()
-    _check(load_library().dta_probe_mfma_bf16(int(n_blocks), int(iters), _ptr(out), _ptr(ticks), _stream(),
-                                              C.byref(flop), C.byref(khz)), "dta_probe_mfma_bf16")
-    return int(flop.value), int(khz.value)
-
-
-def probe_overlap(n_blocks: int, mfma_iters: int, valu_iters: int, out):
-    """dta_probe_overlap on torch's current stream; out is a device fp32 tensor
-    of n_blocks*512 elements."""
-    if out.numel() < n_blocks * 512:
-        raise ValueError("probe buffer too small")
-    _check(load_library().dta_probe_overlap(int(n_blocks), int(mfma_iters), int(valu_iters), _ptr(out), _stream()),
-           "dta_probe_overlap")

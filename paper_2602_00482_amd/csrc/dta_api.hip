@@ -149,7 +149,7 @@ struct Part {
 // One block holding every part (each 256-byte aligned), filled from the host
 // and complete on return.
 int upload_parts(int dev, hipStream_t st, std::initializer_list<Part> parts, void** blob,
-                 size_t* cap) {
+                 size_t* cap, dta_tree* reuse_from = nullptr) {
   size_t total = 0;
   for (const Part& p : parts) total += round_up(p.bytes ? p.bytes : 1, 256);
   std::vector<char> staging;
@@ -158,7 +158,26 @@ int upload_parts(int dev, hipStream_t st, std::initializer_list<Part> parts, voi
   } catch (const std::bad_alloc&) {
     return DTA_ERR_ALLOC;
   }
-  *blob = pool_alloc(dev, total, cap);
+  *blob = nullptr;
+  if (reuse_from) {
+    // a block this tree set aside when it dropped an old segment schedule: launches
+    // in flight may still read it, so the copy is ordered behind the tree's latest launch
+    auto& rl = reuse_from->retired;
+    for (size_t i = 0; i < rl.size(); ++i) {
+      if (rl[i].device != dev || rl[i].cap < total) continue;
+      if (reuse_from->used &&
+          hipStreamWaitEvent(st, (hipEvent_t)reuse_from->last_use, 0) != hipSuccess) {
+        (void)hipGetLastError();
+        break;
+      }
+      *blob = rl[i].ptr;
+      *cap = rl[i].cap;
+      rl[i] = rl.back();
+      rl.pop_back();
+      break;
+    }
+  }
+  if (!*blob) *blob = pool_alloc(dev, total, cap);
   if (!*blob) return DTA_ERR_ALLOC;
   size_t off = 0;
   for (const Part& p : parts) {
@@ -258,7 +277,7 @@ int ensure_device(dta_tree* tree, const dta::TileChoice& tc, const dta_attn_para
                             part_of(s->kv_tiles, &s->d_kv_tiles),
                             part_of(s->kv_items, &s->d_kv_items),
                             part_of(s->kv_reduce, &s->d_kv_reduce)},
-                           &s->d_blob, &s->d_blob_cap)) != DTA_OK)
+                           &s->d_blob, &s->d_blob_cap, t_begin < 0 ? nullptr : tree)) != DTA_OK)
       return st;
     s->device = dev;
   }
@@ -311,6 +330,7 @@ void dta_tree_destroy(dta_tree_t* tree) {
     pool_release(kv.second.device, kv.second.d_blob, kv.second.d_blob_cap, busy);
   for (auto& kv : tree->segment_schedules)
     pool_release(kv.second.device, kv.second.d_blob, kv.second.d_blob_cap, busy);
+  for (auto& rb : tree->retired) pool_release(rb.device, rb.ptr, rb.cap, busy);
   delete tree;
 }
 

@@ -87,6 +87,7 @@ struct Schedule {
   int64_t fwd_chunks64 = 0, fwd_chunks128 = 0;
   // device copies: one allocation (d_blob, owned, released with the tree) that
   // the typed pointers below point into
+  uint64_t last_used = 0;   // segment schedules: the tree's use counter at the latest call
   int device = -1;
   void* d_blob = nullptr;
   size_t d_blob_cap = 0;
@@ -110,8 +111,13 @@ struct dta_tree {
   dta_tree_info_t info{};
   // schedules keyed by (bm, bn, kv heads, group size)
   std::map<uint64_t, dta::Schedule> schedules;
-  // schedules of segment calls, keyed by (tile configuration, t_begin, t_end)
+  // schedules of segment calls, keyed by (tile configuration, t_begin, t_end): at most
+  // dta::kMaxSegmentSchedules of them; beyond that the least recently used one is dropped
+  // and its device block waits in `retired` for the next schedule that fits into it
   std::map<std::array<uint64_t, 3>, dta::Schedule> segment_schedules;
+  uint64_t use_counter = 0;
+  struct RetiredBlock { void* ptr; size_t cap; int device; };
+  std::vector<RetiredBlock> retired;
   int32_t* d_token_kend = nullptr;
   size_t d_kend_cap = 0;
   int kend_device = -1;
@@ -121,6 +127,10 @@ struct dta_tree {
 };
 
 namespace dta {
+
+// Segment schedules a tree keeps (an executor walks a tree's segments over and over, one
+// schedule per distinct row range; 2 x nodes ranges in the push / pop order).
+constexpr size_t kMaxSegmentSchedules = 1024;
 
 // Resident blocks of a launch whose blocks draw work items from queues: the
 // 256 CUs of an MI355X times the blocks of that kernel that fit on a CU.

@@ -4,6 +4,7 @@
 // expanded into the segment calls of this library.  See include/dta.h.
 #include <algorithm>
 #include <cstdint>
+#include <memory>
 #include <new>
 #include <tuple>
 #include <vector>
@@ -48,7 +49,8 @@ int dta_tree_plan(const dta_tree_t* tree, int64_t block, dta_plan_t** out) {
       }
     }
     std::sort(roots.begin(), roots.end(), by_key);
-    auto* p = new dta_plan();
+    std::unique_ptr<dta_plan> owner(new dta_plan());
+    dta_plan* p = owner.get();
     {
       std::vector<int32_t> stack(roots.rbegin(), roots.rend());
       while (!stack.empty()) {
@@ -60,61 +62,73 @@ int dta_tree_plan(const dta_tree_t* tree, int64_t block, dta_plan_t** out) {
       std::reverse(p->leaf_order.begin(), p->leaf_order.end());
     }
 
-    // ---- the schedule over depth ranges of the current leaf's root path
+    // ---- per leaf of that order: its depth and how many tokens of its root path
+    // it shares with the leaf before and after it (the depth of the deepest common node)
     std::vector<int32_t> path_a, path_b;
     auto node_path = [&](int32_t u, std::vector<int32_t>& path) {
       path.clear();
       for (; u >= 0; u = parent[(size_t)u]) path.push_back(u);
       std::reverse(path.begin(), path.end());
     };
-    auto lcp = [&](int32_t a, int32_t b) {
+    auto shared_depth = [&](int32_t a, int32_t b) {
       node_path(a, path_a);
       node_path(b, path_b);
-      int64_t l = 0;
+      int64_t d = 0;
       for (size_t i = 0; i < std::min(path_a.size(), path_b.size()) && path_a[i] == path_b[i]; ++i)
-        l = end_depth(path_a[i]);
-      return l;
+        d = end_depth(path_a[i]);
+      return d;
+    };
+    struct LeafRec { int32_t leaf; int64_t depth, with_prev, with_next; };
+    const size_t NL = p->leaf_order.size();
+    std::vector<LeafRec> recs(NL);
+    for (size_t i = 0; i < NL; ++i) {
+      const int32_t s = p->leaf_order[i];
+      recs[i] = LeafRec{s, end_depth(s), 0, 0};
+      if (i > 0) recs[i].with_prev = recs[i - 1].with_next = shared_depth(p->leaf_order[i - 1], s);
+    }
+
+    // One splitter serves every release of the stack: depths (lo, hi] are cut at
+    // evenly spaced boundaries at most `block` apart, cuts[0] = lo ... cuts[m] = hi.
+    std::vector<int64_t> cuts;
+    auto split = [&](int64_t lo, int64_t hi) {
+      cuts.clear();
+      const int64_t len = hi - lo;
+      const int64_t m = (block <= 0 || len <= block) ? 1 : (len + block - 1) / block;
+      for (int64_t j = 0; j <= m; ++j) cuts.push_back(lo + len * j / m);
     };
     auto emit = [&](int32_t op, int32_t leaf, int64_t lo, int64_t hi) {
       p->ops.push_back(dta_plan_op_t{op, leaf, lo, hi});
     };
-    auto pop_by_chunk = [&](int32_t leaf, int64_t hi, int64_t lo) {
-      const int64_t len = hi - lo;
-      if (len <= 0) return;
-      const int64_t m = (block <= 0 || block >= len) ? 1 : (len + block - 1) / block;
-      for (int64_t j = m - 1; j >= 0; --j) {   // evenly spaced boundaries, last chunk first
-        const int64_t a = lo + len * j / m, b = lo + len * (j + 1) / m;
-        emit(DTA_OP_REFWD, leaf, a, b);
-        emit(DTA_OP_BWD, leaf, a, b);
+    // releases depths (lo, hi] of `leaf`'s path, deepest chunk first; each chunk is
+    // forwarded again (its activations are gone) and then back-propagated
+    auto release = [&](int32_t leaf, int64_t lo, int64_t hi) {
+      if (hi <= lo) return;
+      split(lo, hi);
+      for (size_t j = cuts.size() - 1; j > 0; --j) {
+        emit(DTA_OP_REFWD, leaf, cuts[j - 1], cuts[j]);
+        emit(DTA_OP_BWD, leaf, cuts[j - 1], cuts[j]);
         ++p->n_chunks;
       }
     };
-    int64_t l_backward = 0;
-    const size_t NL = p->leaf_order.size();
     for (size_t i = 0; i < NL; ++i) {
-      const int32_t s = p->leaf_order[i];
-      const int64_t len = end_depth(s);
-      int64_t l_lcp = 0;
-      if (i > 0) {
-        l_lcp = lcp(p->leaf_order[i - 1], s);
-        pop_by_chunk(p->leaf_order[i - 1], l_backward, l_lcp);
-      }
-      emit(DTA_OP_FWD, s, l_lcp, len);
+      const LeafRec& r = recs[i];
+      // what the stack holds beyond the part shared with this leaf goes first
+      if (i > 0) release(recs[i - 1].leaf, r.with_prev, recs[i - 1].depth);
+      emit(DTA_OP_FWD, r.leaf, r.with_prev, r.depth);
       ++p->n_fwd;
-      p->max_stack = std::max(p->max_stack, len);
-      l_backward = len;
-      int64_t l_anchor = i + 1 < NL ? lcp(s, p->leaf_order[i + 1]) : 0;
-      const int64_t p_pop = len - l_anchor;
-      if (block > 0 && p_pop >= block) {
-        const int64_t m = (p_pop + block - 1) / block;
-        l_anchor = len - (p_pop + m - 1) / m;
-      }
-      if (l_lcp < l_anchor) {
-        emit(DTA_OP_FWD_NOGRAD, s, l_lcp, l_anchor);
+      p->max_stack = std::max(p->max_stack, r.depth);
+      // The next release of this leaf's path, (with_next, depth], starts with its
+      // deepest chunk; the keys/values below that chunk's start must be on the
+      // stack without gradient state by then, which is the anchor forward (needed
+      // only where this leaf's own forward started above that point).
+      split(r.with_next, r.depth);
+      const int64_t anchor = cuts[cuts.size() - 2];
+      if (r.with_prev < anchor) {
+        emit(DTA_OP_FWD_NOGRAD, r.leaf, r.with_prev, anchor);
         ++p->n_nograd;
       }
     }
-    if (NL) pop_by_chunk(p->leaf_order[NL - 1], l_backward, 0);
+    if (NL) release(recs[NL - 1].leaf, 0, recs[NL - 1].depth);
 
     // ---- every operation as segment calls: one per node the range touches;
     // forwards root side first, backwards leaf side first
@@ -132,7 +146,7 @@ int dta_tree_plan(const dta_tree_t* tree, int64_t block, dta_plan_t** out) {
       if (op.op == DTA_OP_BWD) std::reverse(p->calls.begin() + (ptrdiff_t)first, p->calls.end());
       p->call_ptr.push_back((int64_t)p->calls.size());
     }
-    *out = p;
+    *out = owner.release();
   } catch (const std::bad_alloc&) {
     return DTA_ERR_ALLOC;
   }

@@ -5,7 +5,7 @@
 // same chip reaches under the same power limit with the same instruction
 // (v_mfma_f32_32x32x16_bf16), the same block shape (4 waves, two blocks per
 // CU) and changing, non-trivial operands.
-#include "dta.h"
+#include "dta_probe.h"
 #include "dta_mfma.h"
 
 namespace dta {

@@ -4,6 +4,7 @@
 // "Load-Balanced DFS-Contiguous Partitioning").  See include/dta.h.
 #include <algorithm>
 #include <cstdint>
+#include <memory>
 #include <new>
 #include <numeric>
 #include <vector>
@@ -40,7 +41,8 @@ int dta_rollouts_build(const int32_t* tokens, const int64_t* seq_offsets, int32_
   for (int32_t i = 0; i < n_seqs; ++i)
     if (seq_offsets[i + 1] <= seq_offsets[i]) return DTA_ERR_INVALID_ARG;   // empty or decreasing
   try {
-    auto* r = new dta_rollouts();
+    std::unique_ptr<dta_rollouts> owner(new dta_rollouts());
+    dta_rollouts* r = owner.get();
     r->n_seqs = n_seqs;
     auto seq = [&](int32_t i) { return tokens + seq_offsets[i]; };
     auto length = [&](int32_t i) { return seq_offsets[i + 1] - seq_offsets[i]; };
@@ -110,10 +112,10 @@ int dta_rollouts_build(const int32_t* tokens, const int64_t* seq_offsets, int32_
       const Node& nd = nodes[(size_t)u];
       new_id[(size_t)u] = (int32_t)r->parent.size();
       r->parent.push_back(nd.parent < 0 ? -1 : new_id[(size_t)nd.parent]);
-      if (nd.end - nd.start > 0x7fffffff) { delete r; return DTA_ERR_BAD_TREE; }
+      if (nd.end - nd.start > 0x7fffffff) return DTA_ERR_BAD_TREE;
       r->seg_len.push_back((int32_t)(nd.end - nd.start));
       total += nd.end - nd.start;
-      if (total > 0x7fffffff) { delete r; return DTA_ERR_BAD_TREE; }   // token count overflow
+      if (total > 0x7fffffff) return DTA_ERR_BAD_TREE;   // token count overflow
       const int32_t* s = seq(r->order[(size_t)nd.rep]);
       r->tokens.insert(r->tokens.end(), s + nd.start, s + nd.end);
       for (auto k = nd.kids.rbegin(); k != nd.kids.rend(); ++k) work.push_back(*k);
@@ -121,7 +123,7 @@ int dta_rollouts_build(const int32_t* tokens, const int64_t* seq_offsets, int32_
     r->seq_node.resize((size_t)n_seqs);
     for (int32_t i = 0; i < n_seqs; ++i)
       r->seq_node[(size_t)r->order[(size_t)i]] = new_id[(size_t)end_node[(size_t)i]];
-    *out = r;
+    *out = owner.release();
   } catch (const std::bad_alloc&) {
     return DTA_ERR_ALLOC;
   }
@@ -147,49 +149,54 @@ int dta_rollouts_partition(const dta_rollouts_t* r, int32_t k, int32_t* group_be
   if (!r || !group_begin || !group_cost) return DTA_ERR_INVALID_ARG;
   const int32_t N = r->n_seqs;
   if (k < 1 || k > N) return DTA_ERR_INVALID_ARG;
-  const std::vector<int64_t>& len = r->len;
-  const std::vector<int64_t>& lcp = r->lcp;
   try {
-    std::vector<int32_t> cuts;   // first index of every group
-    // greedy scan: can the order be cut into at most k groups of cost <= tau?
-    auto feasible = [&](int64_t tau) {
-      cuts.clear();
-      cuts.push_back(0);
-      int64_t c = len[0];
-      for (int32_t i = 1; i < N; ++i) {
-        const int64_t delta = len[(size_t)i] - lcp[(size_t)i];   // new tree tokens added by pi_i
-        if (c + delta > tau) {
-          cuts.push_back(i);
-          c = len[(size_t)i];
-        } else {
-          c += delta;
-        }
-      }
-      return (int32_t)cuts.size() <= k;
+    // grown[i] = tree tokens of the first i sequences of the order taken together
+    // (a sequence adds what it does not share with its predecessor).  A group
+    // [a, b) rebuilt on its own needs the shared part of its first sequence as
+    // well: cost(a, b) = lcp[a] + grown[b] - grown[a].
+    std::vector<int64_t> grown((size_t)N + 1, 0);
+    for (int32_t i = 0; i < N; ++i)
+      grown[(size_t)i + 1] = grown[(size_t)i] + (r->len[(size_t)i] - r->lcp[(size_t)i]);
+    auto cost = [&](int32_t a, int32_t b) {
+      return r->lcp[(size_t)a] + grown[(size_t)b] - grown[(size_t)a];
     };
-    int64_t L = *std::max_element(len.begin(), len.end());
-    int64_t R = len[0];
-    for (int32_t i = 1; i < N; ++i) R += len[(size_t)i] - lcp[(size_t)i];
-    while (L < R) {
-      const int64_t tau = (L + R) / 2;
-      if (feasible(tau)) R = tau;
-      else L = tau + 1;
+    // Filling groups greedily under a cost bound: a group that starts at a runs up
+    // to the last b with cost(a, b) <= bound, found by bisection in the
+    // non-decreasing `grown`.  Returns the number of groups, at most `limit` + 1.
+    std::vector<int32_t> starts;
+    auto fill = [&](int64_t bound, int32_t limit) {
+      starts.clear();
+      for (int32_t a = 0; a < N && (int32_t)starts.size() <= limit;) {
+        starts.push_back(a);
+        const int64_t reach = bound - r->lcp[(size_t)a] + grown[(size_t)a];
+        const int32_t b = (int32_t)(std::upper_bound(grown.begin() + a + 1, grown.end(), reach) - grown.begin()) - 1;
+        a = std::max(b, a + 1);   // the bound is never below the longest sequence, so b > a
+      }
+      return (int32_t)starts.size();
+    };
+    // smallest bound that k groups can meet: between the longest sequence (every
+    // group holds at least one whole sequence) and the whole tree
+    int64_t lo = *std::max_element(r->len.begin(), r->len.end()), hi = grown[(size_t)N];
+    while (lo < hi) {
+      const int64_t mid = lo + (hi - lo) / 2;
+      if (fill(mid, k) <= k) hi = mid;
+      else lo = mid + 1;
     }
-    feasible(L);
-    // split non-singleton groups (the first one, after its first element) until there are k
-    while ((int32_t)cuts.size() < k) {
-      size_t j = 0;
-      while ((j + 1 < cuts.size() ? cuts[j + 1] : N) - cuts[j] < 2) ++j;
-      cuts.insert(cuts.begin() + (ptrdiff_t)j + 1, cuts[j] + 1);
-    }
-    for (int32_t g = 0; g < k; ++g) {
-      const int32_t a = cuts[(size_t)g], b = g + 1 < k ? cuts[(size_t)g + 1] : N;
-      group_begin[g] = a;
-      int64_t c = len[(size_t)a];
-      for (int32_t i = a + 1; i < b; ++i) c += len[(size_t)i] - lcp[(size_t)i];
-      group_cost[g] = c;
+    int32_t spare = k - fill(lo, k);
+    // fewer groups than asked for: single sequences are taken off the front of
+    // the first groups that have more than one (this is the paper's "split any
+    // non-singleton interval", always applied to the first one after its first
+    // sequence)
+    int32_t g = 0;
+    for (size_t j = 0; j < starts.size(); ++j) {
+      const int32_t a = starts[j], b = j + 1 < starts.size() ? starts[j + 1] : N;
+      const int32_t peel = std::min(spare, b - a - 1);
+      for (int32_t t = 0; t < peel; ++t) group_begin[g++] = a + t;
+      group_begin[g++] = a + peel;
+      spare -= peel;
     }
     group_begin[k] = N;
+    for (g = 0; g < k; ++g) group_cost[g] = cost(group_begin[g], group_begin[g + 1]);
   } catch (const std::bad_alloc&) {
     return DTA_ERR_ALLOC;
   }

@@ -187,7 +187,9 @@ Schedule& get_schedule(dta_tree* tree, int bm, int bn, int hkv, int group) {
   const uint64_t key = schedule_key(bm, bn, hkv, group);
   auto it = tree->schedules.find(key);
   if (it != tree->schedules.end()) return it->second;
-  Schedule& s = tree->schedules[key];
+  // built aside and moved into the map when complete: an allocation failure half
+  // way must not leave a partial schedule behind that a later call would use
+  Schedule s;
   s.bm = bm;
   s.bn = bn;
   s.hkv = hkv;
@@ -313,7 +315,7 @@ Schedule& get_schedule(dta_tree* tree, int bm, int bn, int hkv, int group) {
     for (size_t i : order) sorted.push_back(s.kv_items[i]);
     s.kv_items.swap(sorted);
   }
-  return s;
+  return tree->schedules.emplace(key, std::move(s)).first->second;
 }
 
 Schedule& get_segment_schedule(dta_tree* tree, int bm, int bn, int hkv, int group,
@@ -321,8 +323,12 @@ Schedule& get_segment_schedule(dta_tree* tree, int bm, int bn, int hkv, int grou
   const std::array<uint64_t, 3> key = {schedule_key(bm, bn, hkv, group), (uint64_t)t_begin,
                                        (uint64_t)t_end};
   auto it = tree->segment_schedules.find(key);
-  if (it != tree->segment_schedules.end()) return it->second;
-  Schedule& s = tree->segment_schedules[key];
+  if (it != tree->segment_schedules.end()) {
+    it->second.last_used = ++tree->use_counter;
+    return it->second;
+  }
+  Schedule s;   // built aside, see get_schedule
+  s.last_used = ++tree->use_counter;
   s.bm = bm;
   s.bn = bn;
   s.hkv = hkv;
@@ -387,7 +393,18 @@ Schedule& get_segment_schedule(dta_tree* tree, int bm, int bn, int hkv, int grou
     s.kv_items.push_back(KvItem{t.k0, t.k1, t.q_end, t.q_full_end, 0, (int32_t)iters, -1, t.q_begin});
     s.kv_item_iters += iters;
   }
-  return s;
+  // keep the cache bounded: drop the least recently used schedule; its device
+  // block may still be read by a launch in flight, so it is only set aside here
+  // (whoever uploads into it next orders that copy behind the tree's launches)
+  if (tree->segment_schedules.size() >= kMaxSegmentSchedules) {
+    auto lru = tree->segment_schedules.begin();
+    for (auto e = tree->segment_schedules.begin(); e != tree->segment_schedules.end(); ++e)
+      if (e->second.last_used < lru->second.last_used) lru = e;
+    if (lru->second.d_blob)
+      tree->retired.push_back(dta_tree::RetiredBlock{lru->second.d_blob, lru->second.d_blob_cap, lru->second.device});
+    tree->segment_schedules.erase(lru);
+  }
+  return tree->segment_schedules.emplace(key, std::move(s)).first->second;
 }
 
 int validate_params(const dta_attn_params_t* p) {

@@ -10,6 +10,7 @@ import pytest
 import torch
 
 import paper_2602_00482_amd as dta
+from paper_2602_00482_amd import probe
 from oracle import tree_direct as B
 from workloads import make_inputs_numpy, random_tree
 from parity_util import rel_err, run_hip
@@ -151,7 +152,7 @@ def test_mfma_rate_probe_is_linear_in_its_iteration_count():
     for iters in (1, 2, 8):
         out = torch.full((n_blocks * 256,), float("nan"), dtype=torch.float32, device="cuda")
         ticks = torch.zeros(2 * n_blocks, dtype=torch.int64, device="cuda")
-        flop, khz = dta.probe_mfma_bf16(n_blocks, iters, out, ticks)
+        flop, khz = probe.probe_mfma_bf16(n_blocks, iters, out, ticks)
         torch.cuda.synchronize()
         assert flop == n_blocks * 4 * iters * 16 * 2 * 32 * 32 * 16
         assert khz > 0
@@ -167,6 +168,63 @@ def test_overlap_probe_runs_and_writes_every_element():
     out = torch.full((2 * 512,), float("nan"), dtype=torch.float32, device="cuda")
     for m, v in ((3, 0), (0, 3), (3, 3)):
         out.fill_(float("nan"))
-        dta.probe_overlap(2, m, v, out)
+        probe.probe_overlap(2, m, v, out)
         torch.cuda.synchronize()
         assert bool(torch.isfinite(out).all())
+
+
+@pytest.mark.parametrize("dtype,d,Hq,Hkv", [("bf16", 128, 8, 2), ("f32", 64, 4, 2)])
+def test_outputs_with_sentinel_guards_on_both_sides_stay_inside_their_rows(dtype, d, Hq, Hkv):
+    """Every output (and the workspaces) is a window inside a larger allocation
+    filled with a byte pattern; after forward and backward the bytes before and
+    after each window must be untouched.  The tree has a ragged tail in every
+    tile size (T = 1 mod 32) and split key tiles."""
+    rng = np.random.default_rng(23)
+    parent, seg = random_tree(rng, 12, 260, n_roots=2)
+    seg[0] += (1 - int(seg.sum())) % 32          # T = 1 (mod 32)
+    x, t, tree, p, _ = _setup(parent, seg, Hq, Hkv, d, dtype, seed=6)
+    T = int(seg.sum())
+    GUARD = 1 << 16                               # bytes on each side
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+
+    def guarded(shape, dt):
+        n = int(np.prod(shape)) * torch.empty(0, dtype=dt).element_size()
+        raw = torch.full((GUARD + n + GUARD,), 0xA5, dtype=torch.uint8, device="cuda")
+        return raw, raw[GUARD:GUARD + n].view(dt).view(*shape)
+
+    bufs = {name: guarded(shape, dt) for name, shape, dt in (
+        ("o", (T, Hq, d), tdt), ("lse", (T, Hq), torch.float32), ("dq", (T, Hq, d), tdt),
+        ("dk", (T, Hkv, d), tdt), ("dv", (T, Hkv, d), tdt),
+        ("ws_fwd", (max(256, dta.workspace_bytes(tree, p, False)),), torch.uint8),
+        ("ws_bwd", (max(256, dta.workspace_bytes(tree, p, True)),), torch.uint8))}
+    w = {n: b[1] for n, b in bufs.items()}
+    dta.tree_attn_fwd(tree, p, t["q"], t["k"], t["v"], w["o"], w["lse"], w["ws_fwd"])
+    dta.tree_attn_bwd(tree, p, t["q"], t["k"], t["v"], w["o"], w["lse"], t["do"], w["dq"], w["dk"], w["dv"],
+                      w["ws_bwd"])
+    torch.cuda.synchronize()
+    tree.destroy()
+    for name, (raw, win) in bufs.items():
+        assert bool((raw[:GUARD] == 0xA5).all()), f"{name}: bytes before the buffer were written"
+        assert bool((raw[-GUARD:] == 0xA5).all()), f"{name}: bytes after the buffer were written"
+    # and the windows hold the same results as ordinary allocations
+    ref = run_hip(parent, seg, x, Hq, Hkv, d, 1.0 / math.sqrt(d), dtype)
+    for name in ("o", "lse", "dq", "dk", "dv"):
+        assert np.array_equal(w[name].double().cpu().numpy(), ref[name]), name
+
+
+def test_more_segment_ranges_than_the_schedule_cache_holds():
+    """A tree keeps at most 1024 segment schedules; beyond that the least recently
+    used one is dropped and its device block is reused.  1300 one-row forward
+    calls, then the first rows again (their schedules are gone and are rebuilt
+    into recycled blocks): all rows must equal the one-launch forward."""
+    T = 1300
+    x, t, tree, p, _ = _setup([-1], [T], 2, 1, 128, "bf16", seed=8)
+    o_ref, lse_ref = dta.tree_attn_fwd(tree, p, t["q"], t["k"], t["v"])
+    o = torch.zeros_like(o_ref)
+    lse = torch.zeros_like(lse_ref)
+    for r in list(range(T)) + list(range(0, 300)):
+        dta.tree_attn_fwd_segment(tree, p, r, r + 1, t["q"], t["k"], t["v"], o, lse)
+    torch.cuda.synchronize()
+    tree.destroy()
+    assert float((lse - lse_ref).abs().max()) <= 1e-5
+    assert float((o.double() - o_ref.double()).abs().max() / o_ref.double().abs().max()) <= 1e-2

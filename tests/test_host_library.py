@@ -17,12 +17,17 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "dta.h")).read()
-    declared = set(re.findall(r"\b(dta_[a-z0-9_]+)\s*\(", header))
-    assert declared == set(dta.exported_symbols)
+    from paper_2602_00482_amd import probe
+    for hdr, mod in (("dta.h", dta), ("dta_probe.h", probe)):
+        header = open(os.path.join(ROOT, "include", hdr)).read()
+        declared = set(re.findall(r"\b(dta_[a-z0-9_]+)\s*\(", header))
+        assert declared == set(mod.exported_symbols), hdr
+        lib = mod.load_library()
+        for name in declared:
+            assert hasattr(lib, name), name
+    # the measurement kernels are not in the attention library
+    assert not hasattr(dta.load_library(), "dta_probe_mfma_bf16")
     lib = dta.load_library()
-    for name in declared:
-        assert hasattr(lib, name), name
     assert lib.dta_status_string(0) == b"DTA_OK"
     assert lib.dta_status_string(-2) == b"DTA_ERR_BAD_TREE"
 
@@ -159,6 +164,8 @@ def test_error_codes():
     assert lib.dta_tree_attn_bwd_stages(tree.handle, C.byref(good), z, z, z, z, z, z, z, z, z, z, 0, z, 0) == -1
     assert lib.dta_tree_attn_bwd_stages(tree.handle, C.byref(good), z, z, z, z, z, z, z, z, z, z, 0, z, 8) == -1
     # the rate probe checks its arguments before launching anything
+    from paper_2602_00482_amd import probe
+    lib = probe.load_library()
     one = C.c_void_p(1)
     assert lib.dta_probe_mfma_bf16(1, 1, z, one, z, None, None) == -1
     assert lib.dta_probe_mfma_bf16(1, 1, one, z, z, None, None) == -1
@@ -169,7 +176,7 @@ def test_error_codes():
     assert lib.dta_probe_overlap(0, 1, 1, one, z) == -1
     assert lib.dta_probe_overlap(1, -1, 1, one, z) == -1
     assert lib.dta_probe_overlap(1, 1, 2 ** 24 + 1, one, z) == -1
-    lib.dta_tree_destroy(None)
+    dta.load_library().dta_tree_destroy(None)
     tree.destroy()
 
 
