@@ -44,7 +44,7 @@ enum {
   DTA_OK = 0,
   DTA_ERR_INVALID_ARG = -1, /* null pointer, n_nodes < 1, bad struct field         */
   DTA_ERR_BAD_TREE = -2,    /* parent out of range / self parent / cycle / seg_len<1 / > 2^31-1 tokens */
-  DTA_ERR_UNSUPPORTED = -3, /* head_dim not in {64,128}, Hq % Hkv != 0, unknown dtype, bf16 with head_dim 64 */
+  DTA_ERR_UNSUPPORTED = -3, /* head_dim not in {64,128}, Hq % Hkv != 0, unknown dtype */
   DTA_ERR_ALLOC = -4,       /* host or device allocation failed                     */
   DTA_ERR_HIP = -5,         /* a HIP runtime call or kernel launch failed           */
   DTA_ERR_WORKSPACE = -6    /* workspace null or smaller than required              */
@@ -96,7 +96,7 @@ typedef struct {
 typedef struct {
   int32_t n_q_heads;
   int32_t n_kv_heads;   /* must divide n_q_heads; q head h uses kv head h / (n_q_heads/n_kv_heads) */
-  int32_t head_dim;     /* 64 or 128 (DTA_F32), 128 (DTA_BF16)                                     */
+  int32_t head_dim;     /* 64 or 128                                                               */
   float softmax_scale;  /* multiplies q.k before the softmax; finite and nonzero, else INVALID_ARG   */
   int32_t dtype;        /* DTA_F32 or DTA_BF16: element type of q,k,v,o,dO,dq,dk,dv                */
 } dta_attn_params_t;

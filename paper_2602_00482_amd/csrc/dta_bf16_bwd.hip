@@ -32,19 +32,21 @@ __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) {
   return __uint_as_float((uint32_t)b << 16);
 }
 
-// 16 lanes per (token, head) row, 8 elements each.
+// HD / 8 lanes per (token, head) row, 8 elements each.
+template <int HD>
 __global__ __launch_bounds__(256) void delta_bf16_kernel(const uint16_t* __restrict__ o,
                                                          const uint16_t* __restrict__ d_o,
                                                          const float* __restrict__ lse,
                                                          float* __restrict__ neg_delta,
                                                          float* __restrict__ neg_lse_s,
                                                          float inv_scale, size_t rows) {
-  const size_t row = (size_t)blockIdx.x * 16 + (threadIdx.x >> 4);
-  const int j = threadIdx.x & 15;
+  constexpr int kLanes = HD / 8, kRows = 256 / kLanes;   // per row, per block
+  const size_t row = (size_t)blockIdx.x * kRows + threadIdx.x / kLanes;
+  const int j = threadIdx.x % kLanes;
   float s = 0.f;
   if (row < rows) {
-    const uint4 a = *reinterpret_cast<const uint4*>(o + row * kHeadDim + 8 * j);
-    const uint4 b = *reinterpret_cast<const uint4*>(d_o + row * kHeadDim + 8 * j);
+    const uint4 a = *reinterpret_cast<const uint4*>(o + row * HD + 8 * j);
+    const uint4 b = *reinterpret_cast<const uint4*>(d_o + row * HD + 8 * j);
     const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -55,7 +57,7 @@ __global__ __launch_bounds__(256) void delta_bf16_kernel(const uint16_t* __restr
   s += __shfl_xor(s, 1);
   s += __shfl_xor(s, 2);
   s += __shfl_xor(s, 4);
-  s += __shfl_xor(s, 8);
+  if (HD == 128) s += __shfl_xor(s, 8);
   // Stored negated, and lse divided by the softmax scale: the dK/dV kernel
   // starts its score and dP accumulators from these values, so that
   // P = exp(scale * acc) and dS = P * acc need no further subtraction.
@@ -69,6 +71,7 @@ constexpr int kDqThreads = 512;
 
 // Query-stationary dQ: 8 waves, each 32 query rows of one q head (same walk and
 // wave layout as the forward kernel).
+template <int HD>
 __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
     const QTile* __restrict__ tiles, const KeySeg* __restrict__ segs,
     const int32_t* __restrict__ kend, const uint16_t* __restrict__ q,
@@ -76,15 +79,19 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
     const uint16_t* __restrict__ d_o, const float* __restrict__ lse,
     const uint16_t* __restrict__ o, float* __restrict__ neg_delta, float* __restrict__ neg_lse_s,
     uint16_t* __restrict__ dq, int Hq, int Hkv, int HB, int hblocks, float scale) {
+  using TL = TileLayout<HD>;
+  constexpr int kTileElems = TL::kTileElems, kHeadDim = HD;
+  constexpr int KS = TL::kSteps;   // products per phase: k-steps over head_dim = 2 x output blocks
   __shared__ __attribute__((aligned(1024))) uint16_t Ks[2][kTileElems];
   __shared__ __attribute__((aligned(1024))) uint16_t Vs[2][kTileElems];
   __shared__ __attribute__((aligned(16))) int32_t kendS[2][kKeyChunk];
-  // The last k-step of this wave's Q and dO operands lives in LDS instead of
-  // registers (each lane reads back what it wrote): with all 16 in registers the
-  // kernel needs a few more than 256, and reloads from scratch memory would wait
-  // for, i.e. serialise, the tile copies in flight.
-  constexpr int kReg = 6;
-  __shared__ __attribute__((aligned(16))) uint16_t stashS[kDqThreads / 64][2 * (8 - kReg)][64 * 8];
+  // With head_dim 128 the last two k-steps of this wave's Q and dO operands live in
+  // LDS instead of registers (each lane reads back what it wrote): with all 16 in
+  // registers the kernel needs a few more than 256, and reloads from scratch
+  // memory would wait for, i.e. serialise, the tile copies in flight.
+  constexpr int kReg = HD == 128 ? 6 : KS;
+  constexpr int kStash = KS - kReg;
+  __shared__ __attribute__((aligned(16))) uint16_t stashS[kDqThreads / 64][kStash ? 2 * kStash : 1][64 * 8];
 
   const int inner = blockIdx.x % (Hkv * hblocks);
   const QTile tile = tiles[blockIdx.x / (Hkv * hblocks)];
@@ -105,12 +112,12 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
   // block): D = dO . O, summed in that kernel's order so that the value is the
   // same to the last bit, and the two row statistics are left in the workspace
   // for the dK/dV launch that follows.
-  float dpart[8];
+  float dpart[KS];
   {
     const uint16_t* qp = q + rh * kHeadDim + 8 * hh;
     const uint16_t* dop = d_o + rh * kHeadDim + 8 * hh;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
+    for (int ks = 0; ks < KS; ++ks) {
       const bf16x8 qx = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
       const bf16x8 dx = *reinterpret_cast<const bf16x8*>(dop + 16 * ks);
       if (o != nullptr) {
@@ -142,12 +149,12 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
   const float nlse = -lse[rh] / scale;
   float ndlt;
   if (o != nullptr) {
-    // delta_bf16_kernel's tree over 16 lanes of 8 elements: lane 2*ks + hh there
+    // delta_bf16_kernel's tree over HD / 8 lanes of 8 elements: lane 2*ks + hh there
     // is k-step ks of lane half hh here
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) dpart[ks] += __shfl_xor(dpart[ks], 32);
-    const float d = ((dpart[0] + dpart[1]) + (dpart[2] + dpart[3])) +
-                    ((dpart[4] + dpart[5]) + (dpart[6] + dpart[7]));
+    for (int ks = 0; ks < KS; ++ks) dpart[ks] += __shfl_xor(dpart[ks], 32);
+    float d = (dpart[0] + dpart[1]) + (dpart[2] + dpart[3]);
+    if constexpr (HD == 128) d += (dpart[KS - 4] + dpart[KS - 3]) + (dpart[KS - 2] + dpart[KS - 1]);
     ndlt = -d;
     if (hh == 0 && row_base + c < tile.t1) {
       neg_delta[rh] = ndlt;
@@ -157,9 +164,9 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
     ndlt = neg_delta[rh];
   }
 
-  f32x16 dQ[4];
+  f32x16 dQ[TL::kBlocks];
 #pragma unroll
-  for (int a = 0; a < 4; ++a)
+  for (int a = 0; a < TL::kBlocks; ++a)
 #pragma unroll
     for (int e = 0; e < 16; ++e) dQ[a][e] = 0.f;
 
@@ -176,16 +183,16 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
   auto issue = [&](int b) {
     if (!full || n < kKeyChunk) {   // rare: a chunk that needs the visibility mask
       if (threadIdx.x < kKeyChunk) {   // kendS is indexed by matrix position
-        const int row = row_of_pos(threadIdx.x);
+        const int row = TL::row_of_pos(threadIdx.x);
         kendS[b][threadIdx.x] = row >= n ? 0 : (full ? 0x7fffffff : kend[c0 + row]);
       }
     }
-    tile_async_load<kDqThreads>(Ks[b], kbase + (size_t)c0 * kv_stride, kv_bytes, n);
-    tile_async_load<kDqThreads>(Vs[b], vbase + (size_t)c0 * kv_stride, kv_bytes, n);
+    tile_async_load<kDqThreads, HD>(Ks[b], kbase + (size_t)c0 * kv_stride, kv_bytes, n);
+    tile_async_load<kDqThreads, HD>(Vs[b], vbase + (size_t)c0 * kv_stride, kv_bytes, n);
   };
   issue(0);
   int buf = 0;
-  const int rlo = row_lane_off(), clo = col_lane_off();
+  const int rlo = TL::row_lane_off(), clo = TL::col_lane_off();
 
   while (have) {
     async_wait_all();
@@ -198,8 +205,8 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
     const uint16_t* Vt = Vs[buf] + rlo;
     const uint16_t* Kc = Ks[buf] + clo;
 
-    // The chunk's two 32-key halves as one sequence of 48 matrix products in
-    // six phases, in an issue order written out by hand (a scheduling barrier
+    // The chunk's two 32-key halves as one sequence of 6 x KS matrix products (48
+    // with head_dim 128) in six phases, in an issue order written out by hand (a scheduling barrier
     // after every product keeps it):
     //   S0 | dP0 + exp(S0) | S1 + dS0 | dP1 + exp(S1) | dQ0 + dS1 | dQ1
     // The LDS operand of product i + kAhead is read before product i is issued,
@@ -218,14 +225,15 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
       else if constexpr (ph == 1 || ph == 3) return tile_row8(Vt, ph >> 1, j);
       else return tile_col8(Kc, 32 * (ph - 4) + 16 * (j & 1), 32 * (j >> 1));
     };
+    constexpr int VP = 16 / KS;   // accumulator values whose vector work runs under one product
     auto phase = [&](auto ph_c) {
       constexpr int ph = decltype(ph_c)::value;
       constexpr int mb = (ph >> 1) & 1;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const int i = 8 * ph + j;   // product number in the chunk
-        if (j + kAhead < 8) a[(i + kAhead) % kRing] = fetch(ph_c, j + kAhead);
-        else if (ph < 5) a[(i + kAhead) % kRing] = fetch(std::integral_constant<int, (ph < 5 ? ph + 1 : 5)>{}, j + kAhead - 8);
+      for (int j = 0; j < KS; ++j) {
+        const int i = KS * ph + j;   // product number in the chunk
+        if (j + kAhead < KS) a[(i + kAhead) % kRing] = fetch(ph_c, j + kAhead);
+        else if (ph < 5) a[(i + kAhead) % kRing] = fetch(std::integral_constant<int, (ph < 5 ? ph + 1 : 5)>{}, j + kAhead - KS);
         const bf16x8 av = a[i % kRing];
         if constexpr (ph == 0 || ph == 2) {          // S(mb), starting from -lse/scale
           if (j == 0) {
@@ -239,15 +247,18 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
             for (int e = 0; e < 16; ++e) dP[mb][e] = ndlt;
           }
           dP[mb] = mfma32(av, do_op(j), dP[mb]);
-          S[mb][2 * j] = __builtin_amdgcn_exp2f(S[mb][2 * j] * sc);
-          S[mb][2 * j + 1] = __builtin_amdgcn_exp2f(S[mb][2 * j + 1] * sc);
+#pragma unroll
+          for (int t = 0; t < VP; ++t) S[mb][VP * j + t] = __builtin_amdgcn_exp2f(S[mb][VP * j + t] * sc);
         } else {                                     // dQ
           dQ[j >> 1] = mfma32(av, dSb[ph - 4][j & 1], dQ[j >> 1]);
         }
         if constexpr (ph == 2 || ph == 4) {          // dS of the previous half = P * dP, two values per product
           constexpr int pv = (ph - 2) >> 1;
-          dSb[pv][j >> 2][2 * (j & 3)] = (__bf16)(S[pv][2 * j] * dP[pv][2 * j]);
-          dSb[pv][j >> 2][2 * (j & 3) + 1] = (__bf16)(S[pv][2 * j + 1] * dP[pv][2 * j + 1]);
+#pragma unroll
+          for (int t = 0; t < VP; ++t) {
+            const int e = VP * j + t;
+            dSb[pv][e >> 3][e & 7] = (__bf16)(S[pv][e] * dP[pv][e]);
+          }
         }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -260,7 +271,7 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj) {
               const int e = 4 * e4 + jj;
-              const bool ok = (cc0 + row_of_acc(mb, e, hh) <= qrow) & (qrow < kev[jj]);
+              const bool ok = (cc0 + TL::row_of_acc(mb, e, hh) <= qrow) & (qrow < kev[jj]);
               S[mb][e] = ok ? S[mb][e] : 0.f;
             }
           }
@@ -283,7 +294,7 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
   if (token < tile.t1) {
     uint16_t* op = dq + ((size_t)token * Hq + h) * kHeadDim + 4 * hh;
 #pragma unroll
-    for (int dmb = 0; dmb < 4; ++dmb)
+    for (int dmb = 0; dmb < TL::kBlocks; ++dmb)
 #pragma unroll
       for (int v4 = 0; v4 < 4; ++v4) {
         bf16x4 r;
@@ -300,6 +311,7 @@ constexpr int kKvTile = 128;   // keys per dK/dV tile (32 per wave)
 // Key-stationary dK/dV: 4 waves, 32 key columns each, K and V rows in
 // registers.  Two blocks share a CU (everything fits in 256 registers), so one
 // block's global loads and barriers are covered by the other's matrix work.
+template <int HD>
 __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
     const KvItem* __restrict__ items, const int32_t* __restrict__ kend,
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
@@ -308,20 +320,23 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
     uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, float* __restrict__ partial,
     float* __restrict__ dk_acc, float* __restrict__ dv_acc, int Hq, int Hkv, float scale,
     int* __restrict__ tickets, int n_items) {
+  using TL = TileLayout<HD>;
+  constexpr int kTileElems = TL::kTileElems, kHeadDim = HD;
+  constexpr int KS = TL::kSteps, DB = TL::kBlocks;
   // One object, so that every tile read is "per-lane base + compile-time offset".
-  // The last k-steps of this wave's K and V operands (kStashK and kStashV of the
-  // 8) live in LDS instead of registers, and so do the per-lane mask bounds
-  // (key position, end of its visibility): with all of them in registers the
-  // kernel needs a few more than 256, and the compiler's scratch reloads (vector
-  // memory) would wait for, i.e. serialise, the tile copies in flight.  Each lane
-  // reads back only what it wrote itself.
-  constexpr int kStashK = 1, kStashV = 2;
-  constexpr int kRegK = 8 - kStashK, kRegV = 8 - kStashV;
+  // With head_dim 128 the last k-steps of this wave's K and V operands (kStashK
+  // and kStashV of the 8) live in LDS instead of registers, and so do the
+  // per-lane mask bounds (key position, end of its visibility): with all of them
+  // in registers the kernel needs a few more than 256, and the compiler's scratch
+  // reloads (vector memory) would wait for, i.e. serialise, the tile copies in
+  // flight.  Each lane reads back only what it wrote itself.
+  constexpr int kStashK = HD == 128 ? 1 : 0, kStashV = HD == 128 ? 2 : 0;
+  constexpr int kRegK = KS - kStashK, kRegV = KS - kStashV;
   struct Smem {
     uint16_t Q[2][kTileElems];
     uint16_t dO[2][kTileElems];
     float stat[2][2][kBQ];   // [buffer][-lse/scale | -delta][position]
-    uint16_t stash[4][kStashK + kStashV][64 * 8];
+    uint16_t stash[4][kStashK + kStashV ? kStashK + kStashV : 1][64 * 8];
     int2 bound[kKvThreads];
   };
   __shared__ __attribute__((aligned(256))) Smem sm;
@@ -363,7 +378,7 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
     const uint16_t* kp = k + ((size_t)kc * Hkv + g) * kHeadDim + 8 * hh;
     const uint16_t* vp = v + ((size_t)kc * Hkv + g) * kHeadDim + 8 * hh;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
+    for (int ks = 0; ks < KS; ++ks) {
       const bf16x8 kx = *reinterpret_cast<const bf16x8*>(kp + 16 * ks);
       const bf16x8 vx = *reinterpret_cast<const bf16x8*>(vp + 16 * ks);
       if (ks < kRegK) Kr[ks < kRegK ? ks : 0] = kx;
@@ -372,9 +387,9 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
       else *reinterpret_cast<bf16x8*>(stash + (kStashK + ks - kRegV) * 512) = vx;
     }
   }
-  f32x16 dK[4], dV[4];
+  f32x16 dK[DB], dV[DB];
 #pragma unroll
-  for (int a = 0; a < 4; ++a)
+  for (int a = 0; a < DB; ++a)
 #pragma unroll
     for (int e = 0; e < 16; ++e) { dK[a][e] = 0.f; dV[a][e] = 0.f; }
 
@@ -396,15 +411,15 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
     const int r0 = tile.q_begin + ch * kBQ;
     const int nv = min(kBQ, tile.q_end - r0);
     if (__builtin_amdgcn_readfirstlane(w) == 0) {   // stat is indexed by matrix position
-      const uint32_t off = (uint32_t)min(row_of_pos(l), nv - 1) * (uint32_t)Hq;
+      const uint32_t off = (uint32_t)min(TL::row_of_pos(l), nv - 1) * (uint32_t)Hq;
       row_async_load(sm.stat[b][0], neg_lse_s + (size_t)r0 * Hq + h, off);
       row_async_load(sm.stat[b][1], neg_delta + (size_t)r0 * Hq + h, off);
     }
-    tile_async_load<kKvThreads>(sm.Q[b], q + (size_t)r0 * q_stride + (size_t)h * kHeadDim, q_bytes, nv);
-    tile_async_load<kKvThreads>(sm.dO[b], d_o + (size_t)r0 * q_stride + (size_t)h * kHeadDim, q_bytes, nv);
+    tile_async_load<kKvThreads, HD>(sm.Q[b], q + (size_t)r0 * q_stride + (size_t)h * kHeadDim, q_bytes, nv);
+    tile_async_load<kKvThreads, HD>(sm.dO[b], d_o + (size_t)r0 * q_stride + (size_t)h * kHeadDim, q_bytes, nv);
   };
   if (tile.it_begin < total) issue(tile.it_begin, 0);
-  const int rlo = row_lane_off(), clo = col_lane_off();
+  const int rlo = TL::row_lane_off(), clo = TL::col_lane_off();
 
   // one step of the walk; the buffer index is a compile-time constant
   auto step = [&](int it, auto buf_c) {
@@ -453,8 +468,9 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
         return ks < kRegV ? Vr[ks < kRegV ? ks : 0]
                           : *reinterpret_cast<const bf16x8*>(stash + (kStashK + ks - kRegV) * 512);
       };
+      constexpr int VP = 16 / KS;   // accumulator values whose vector work runs under one product
       f32x16 S, dP;
-      bf16x8 a[8];
+      bf16x8 a[KS];
       // ---- phase 1
 #pragma unroll
       for (int e4 = 0; e4 < 4; ++e4) {
@@ -466,8 +482,8 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
       for (int ks = 0; ks < kAhead; ++ks) a[ks] = tile_row8(Qt, mq, ks);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        if (ks + kAhead < 8) a[ks + kAhead] = tile_row8(Qt, mq, ks + kAhead);
+      for (int ks = 0; ks < KS; ++ks) {
+        if (ks + kAhead < KS) a[ks + kAhead] = tile_row8(Qt, mq, ks + kAhead);
         S = mfma32(a[ks], k_op(ks), S);
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -482,21 +498,22 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
       for (int ks = 0; ks < kAhead; ++ks) a[ks] = tile_row8(dOt, mq, ks);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        if (ks + kAhead < 8) a[ks + kAhead] = tile_row8(dOt, mq, ks + kAhead);
+      for (int ks = 0; ks < KS; ++ks) {
+        if (ks + kAhead < KS) a[ks + kAhead] = tile_row8(dOt, mq, ks + kAhead);
         dP = mfma32(a[ks], v_op(ks), dP);
-        S[2 * ks] = __builtin_amdgcn_exp2f(S[2 * ks] * sc);
-        S[2 * ks + 1] = __builtin_amdgcn_exp2f(S[2 * ks + 1] * sc);
+#pragma unroll
+        for (int t = 0; t < VP; ++t) S[VP * ks + t] = __builtin_amdgcn_exp2f(S[VP * ks + t] * sc);
         __builtin_amdgcn_sched_barrier(0);
       }
       if (need_mask) {   // query row t sees this lane's key iff kcol <= t < kend[kcol]
-        // row_of_acc(mq, e, hh) = 4*hh + (compile-time part): compare against per-lane bounds
+        // row_of_acc(mq, e, hh) = kHalf*hh + (compile-time part): compare against per-lane bounds
+        constexpr int kHalf = TL::row_of_acc(0, 0, 1) - TL::row_of_acc(0, 0, 0);
         const int2 bnd = sm.bound[tid_now];
-        const int lo = bnd.x - r0 - 4 * hh;
-        const int hi = min(bnd.y - r0, nv) - 4 * hh;
+        const int lo = bnd.x - r0 - kHalf * hh;
+        const int hi = min(bnd.y - r0, nv) - kHalf * hh;
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          const int rc = row_of_acc(mq, e, 0);
+          const int rc = TL::row_of_acc(mq, e, 0);
           S[e] = ((rc >= lo) & (rc < hi)) ? S[e] : 0.f;
         }
       }
@@ -507,12 +524,15 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
       for (int i = 0; i < kAhead; ++i) a[i] = tile_col8(dOc, 32 * mq + 16 * (i & 1), 32 * (i >> 1));
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        if (i + kAhead < 8)
+      for (int i = 0; i < KS; ++i) {
+        if (i + kAhead < KS)
           a[i + kAhead] = tile_col8(dOc, 32 * mq + 16 * ((i + kAhead) & 1), 32 * ((i + kAhead) >> 1));
         dV[i >> 1] = mfma32(a[i], Pb[i & 1], dV[i >> 1]);
-        dSb[i >> 2][2 * (i & 3)] = (__bf16)(dP[2 * i] * S[2 * i]);
-        dSb[i >> 2][2 * (i & 3) + 1] = (__bf16)(dP[2 * i + 1] * S[2 * i + 1]);
+#pragma unroll
+        for (int t = 0; t < VP; ++t) {
+          const int e = VP * i + t;
+          dSb[e >> 3][e & 7] = (__bf16)(dP[e] * S[e]);
+        }
         __builtin_amdgcn_sched_barrier(0);
       }
       // ---- phase 4
@@ -520,8 +540,8 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
       for (int i = 0; i < kAhead; ++i) a[i] = tile_col8(Qc, 32 * mq + 16 * (i & 1), 32 * (i >> 1));
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        if (i + kAhead < 8)
+      for (int i = 0; i < KS; ++i) {
+        if (i + kAhead < KS)
           a[i + kAhead] = tile_col8(Qc, 32 * mq + 16 * ((i + kAhead) & 1), 32 * ((i + kAhead) >> 1));
         dK[i >> 1] = mfma32(a[i], dSb[i & 1], dK[i >> 1]);
         __builtin_amdgcn_sched_barrier(0);
@@ -546,7 +566,7 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
                 (size_t)(32 * w + c) * kHeadDim + 4 * hh;
     float* pv = pk + kKvTile * kHeadDim;
 #pragma unroll
-    for (int dmb = 0; dmb < 4; ++dmb)
+    for (int dmb = 0; dmb < DB; ++dmb)
 #pragma unroll
       for (int v4 = 0; v4 < 4; ++v4) {
         f32x4 rk, rv;
@@ -561,7 +581,7 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
     if (kcol < tile.k1) {
       const size_t base = ((size_t)kcol * Hkv + g) * kHeadDim + 4 * hh;
 #pragma unroll
-      for (int dmb = 0; dmb < 4; ++dmb)
+      for (int dmb = 0; dmb < DB; ++dmb)
 #pragma unroll
         for (int v4 = 0; v4 < 4; ++v4) {
           f32x4 rk = *reinterpret_cast<const f32x4*>(dk_acc + base + 32 * dmb + 8 * v4);
@@ -578,7 +598,7 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
   } else if (kcol < tile.k1) {
     const size_t base = ((size_t)kcol * Hkv + g) * kHeadDim + 4 * hh;
 #pragma unroll
-    for (int dmb = 0; dmb < 4; ++dmb)
+    for (int dmb = 0; dmb < DB; ++dmb)
 #pragma unroll
       for (int v4 = 0; v4 < 4; ++v4) {
         bf16x4 rk, rv;
@@ -602,6 +622,7 @@ __global__ void zero_i32_kernel(int* __restrict__ p, int n) {
 }
 
 // Adds the partial sums of a split key tile in slot order and writes dK/dV.
+template <int HD>
 __global__ __launch_bounds__(256) void dkdv_reduce_kernel(const KvReduce* __restrict__ red,
                                                           const float* __restrict__ partial,
                                                           uint16_t* __restrict__ dk,
@@ -611,6 +632,7 @@ __global__ __launch_bounds__(256) void dkdv_reduce_kernel(const KvReduce* __rest
   // tiles fills the chip
   const int sub = blockIdx.x & 7;
   const KvReduce r = red[(blockIdx.x >> 3) / Hkv];
+  constexpr int kHeadDim = HD;
   const int g = (blockIdx.x >> 3) % Hkv;
   const size_t slot_stride = (size_t)Hkv * (2 * kKvTile * kHeadDim);
   const float* base = partial + ((size_t)r.first_slot * Hkv + g) * (2 * kKvTile * kHeadDim);
@@ -636,7 +658,9 @@ __global__ __launch_bounds__(256) void dkdv_reduce_kernel(const KvReduce* __rest
 
 }  // namespace
 
-int launch_bwd_bf16(const LaunchArgs& a) {
+template <int HD>
+int launch_bwd_bf16_hd(const LaunchArgs& a) {
+  constexpr int kHeadDim = HD;
   hipStream_t st = (hipStream_t)a.stream;
   clear_hip_error();
   // rows of (token, q head) the call covers: all of them, or one segment's
@@ -648,13 +672,14 @@ int launch_bwd_bf16(const LaunchArgs& a) {
   // the dQ launch computes the row statistics itself when both stages are asked for
   const bool fused_delta = (a.stages & DTA_BWD_DELTA) && (a.stages & DTA_BWD_DQ);
   if ((a.stages & DTA_BWD_DELTA) && !fused_delta) {
-    delta_bf16_kernel<<<(unsigned)((rows + 15) / 16), 256, 0, st>>>(
+    constexpr size_t kDeltaRows = 256 / (HD / 8);   // rows per block of the delta kernel
+    delta_bf16_kernel<HD><<<(unsigned)((rows + kDeltaRows - 1) / kDeltaRows), 256, 0, st>>>(
         (const uint16_t*)a.o + row0 * kHeadDim, (const uint16_t*)a.d_o + row0 * kHeadDim,
         a.lse_in + row0, a.delta + row0, a.lse2 + row0, 1.f / a.p.softmax_scale, rows);
     { int ls = launch_status(__func__); if (ls != DTA_OK) return ls; }
   }
   if (a.stages & DTA_BWD_DQ) {
-    dq_bf16_kernel<<<(unsigned)qblocks, kDqThreads, 0, st>>>(
+    dq_bf16_kernel<HD><<<(unsigned)qblocks, kDqThreads, 0, st>>>(
         a.sched->d_q_tiles, a.sched->d_segs, a.d_kend, (const uint16_t*)a.q, (const uint16_t*)a.k,
         (const uint16_t*)a.v, (const uint16_t*)a.d_o, a.lse_in,
         fused_delta ? (const uint16_t*)a.o : nullptr, a.delta, a.lse2, (uint16_t*)a.dq,
@@ -678,20 +703,24 @@ int launch_bwd_bf16(const LaunchArgs& a) {
       zero_i32_kernel<<<1, 256, 0, st>>>(tickets, a.p.n_kv_heads);
       { int ls = launch_status(__func__); if (ls != DTA_OK) return ls; }
     }
-    dkdv_bf16_kernel<<<(unsigned)(queues ? resident : kblocks), kKvThreads, 0, st>>>(
+    dkdv_bf16_kernel<HD><<<(unsigned)(queues ? resident : kblocks), kKvThreads, 0, st>>>(
         a.sched->d_kv_items, a.d_kend, (const uint16_t*)a.q, (const uint16_t*)a.k,
         (const uint16_t*)a.v, (const uint16_t*)a.d_o, a.lse2, a.delta, (uint16_t*)a.dk,
         (uint16_t*)a.dv, a.partial, a.dk_acc, a.dv_acc, a.p.n_q_heads, a.p.n_kv_heads,
         a.p.softmax_scale, queues ? tickets : nullptr, (int)a.sched->kv_items.size());
     { int ls = launch_status(__func__); if (ls != DTA_OK) return ls; }
     if (!a.sched->kv_reduce.empty()) {
-      dkdv_reduce_kernel<<<(unsigned)(a.sched->kv_reduce.size() * a.p.n_kv_heads * 8), 256, 0, st>>>(
+      dkdv_reduce_kernel<HD><<<(unsigned)(a.sched->kv_reduce.size() * a.p.n_kv_heads * 8), 256, 0, st>>>(
           a.sched->d_kv_reduce, a.partial, (uint16_t*)a.dk, (uint16_t*)a.dv, a.p.n_kv_heads,
           a.p.softmax_scale);
       { int ls = launch_status(__func__); if (ls != DTA_OK) return ls; }
     }
   }
   return DTA_OK;
+}
+
+int launch_bwd_bf16(const LaunchArgs& a) {
+  return a.p.head_dim == 128 ? launch_bwd_bf16_hd<128>(a) : launch_bwd_bf16_hd<64>(a);
 }
 
 }  // namespace dta

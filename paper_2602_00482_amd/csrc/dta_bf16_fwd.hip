@@ -39,14 +39,16 @@ __device__ __forceinline__ float max_across_halves(float x) {
 // barrier, one round of bookkeeping and one online-softmax step per chunk, so
 // long key intervals run faster with 128, while every interval is padded to a
 // multiple of the chunk, so forests of short segments want 64.
-template <int kCh>
+template <int kCh, int HD>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void fwd_bf16_kernel(
     const QTile* __restrict__ tiles, const KeySeg* __restrict__ segs,
     const int32_t* __restrict__ kend, const uint16_t* __restrict__ q,
     const uint16_t* __restrict__ k, const uint16_t* __restrict__ v, uint16_t* __restrict__ o,
     float* __restrict__ lse, int Hq, int Hkv, int HB, int hblocks, float scale,
     int* __restrict__ tickets, int n_items) {
-  constexpr int kSub = kCh / 64;
+  using TL = TileLayout<HD>;
+  constexpr int kSub = kCh / 64, kTileElems = TL::kTileElems, kHeadDim = HD;
+  constexpr int KS = TL::kSteps, DB = TL::kBlocks;   // k-steps over head_dim, 32-wide output blocks
   __shared__ __attribute__((aligned(1024))) uint16_t Ks[2][kSub][kTileElems];
   __shared__ __attribute__((aligned(1024))) uint16_t Vs[2][kSub][kTileElems];
   __shared__ __attribute__((aligned(16))) int32_t kendS[2][kCh];
@@ -73,11 +75,11 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
   const float sc = fabsf(scale) * kLog2e;
 
   const int qrow = min(row_base + c, tile.t1 - 1);
-  bf16x8 Qr[8];
+  bf16x8 Qr[KS];
   {
     const uint16_t* qp = q + ((size_t)qrow * Hq + h) * kHeadDim + 8 * hh;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
+    for (int ks = 0; ks < KS; ++ks) {
       uint4 raw = *reinterpret_cast<const uint4*>(qp + 16 * ks);
       if (scale < 0.f) {
         raw.x ^= 0x80008000u; raw.y ^= 0x80008000u; raw.z ^= 0x80008000u; raw.w ^= 0x80008000u;
@@ -86,9 +88,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
     }
   }
 
-  f32x16 O[4];
+  f32x16 O[DB];
 #pragma unroll
-  for (int a = 0; a < 4; ++a)
+  for (int a = 0; a < DB; ++a)
 #pragma unroll
     for (int e = 0; e < 16; ++e) O[a][e] = 0.f;
   float m = -INFINITY, lsum = 0.f;   // running max of unscaled scores, partial row sum
@@ -107,7 +109,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
   auto issue = [&](int b) {
     if (!full || n < kCh) {   // rare: a chunk that needs the visibility mask
       if (threadIdx.x < kCh) {   // kendS is indexed by matrix position within each 64-key half
-        const int row = 64 * (threadIdx.x >> 6) + row_of_pos(threadIdx.x & 63);
+        const int row = 64 * (threadIdx.x >> 6) + TL::row_of_pos(threadIdx.x & 63);
         kendS[b][threadIdx.x] = row >= n ? 0 : (full ? 0x7fffffff : kend[c0 + row]);
       }
     }
@@ -117,13 +119,13 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
       const int nv = n - 64 * sub;
       const int r0 = nv > 0 ? c0 + 64 * sub : c0;
       const int nvalid = nv > 0 ? min(nv, 64) : 1;
-      tile_async_load<kThreads>(Ks[b][sub], kbase + (size_t)r0 * kv_stride, kv_bytes, nvalid);
-      tile_async_load<kThreads>(Vs[b][sub], vbase + (size_t)r0 * kv_stride, kv_bytes, nvalid);
+      tile_async_load<kThreads, HD>(Ks[b][sub], kbase + (size_t)r0 * kv_stride, kv_bytes, nvalid);
+      tile_async_load<kThreads, HD>(Vs[b][sub], vbase + (size_t)r0 * kv_stride, kv_bytes, nvalid);
     }
   };
   issue(0);
   int buf = 0;
-  const int rlo = row_lane_off(), clo = col_lane_off();
+  const int rlo = TL::row_lane_off(), clo = TL::col_lane_off();
 
   while (have) {
     async_wait_all();
@@ -144,7 +146,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
 #pragma unroll
     for (int sub = 0; sub < kSub; ++sub)
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
+      for (int ks = 0; ks < KS; ++ks) {
         const bf16x8 a0 = tile_row8(Kt + sub * kTileElems, 0, ks);
         const bf16x8 a1 = tile_row8(Kt + sub * kTileElems, 1, ks);
         S[2 * sub] = mfma32(a0, Qr[ks], S[2 * sub]);
@@ -164,7 +166,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
           const int kev[4] = {ke.x, ke.y, ke.z, ke.w};
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
-            const bool ok = (cc0 + 64 * (mb >> 1) + row_of_acc(mb & 1, 4 * e4 + j, hh) <= qrow) & (qrow < kev[j]);
+            const bool ok = (cc0 + 64 * (mb >> 1) + TL::row_of_acc(mb & 1, 4 * e4 + j, hh) <= qrow) & (qrow < kev[j]);
             S[mb][4 * e4 + j] = ok ? S[mb][4 * e4 + j] : -INFINITY;
           }
         }
@@ -199,7 +201,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
     // the accumulators are rescaled only when some row's running max moved
     if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {
 #pragma unroll
-      for (int dmb = 0; dmb < 4; ++dmb)
+      for (int dmb = 0; dmb < DB; ++dmb)
 #pragma unroll
         for (int e = 0; e < 16; ++e) O[dmb][e] *= alpha;
     }
@@ -210,7 +212,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
 #pragma unroll
-        for (int dmb = 0; dmb < 4; ++dmb) {
+        for (int dmb = 0; dmb < DB; ++dmb) {
           const bf16x8 va = tile_col8(Vt + sub * kTileElems, 16 * kk, 32 * dmb);
           O[dmb] = mfma32(va, Pb[4 * sub + kk], O[dmb]);
         }
@@ -226,7 +228,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))
   if (token < tile.t1) {
     uint16_t* op = o + ((size_t)token * Hq + h) * kHeadDim + 4 * hh;
 #pragma unroll
-    for (int dmb = 0; dmb < 4; ++dmb)
+    for (int dmb = 0; dmb < DB; ++dmb)
 #pragma unroll
       for (int v4 = 0; v4 < 4; ++v4) {
         bf16x4 r;
@@ -264,7 +266,8 @@ int launch_fwd_bf16(const LaunchArgs& a) {
   // at most 6 % to the keys streamed (measured: 5 % faster at +0.5 %, 1.4 % faster
   // at +5.6 %, 2 % slower at +9.6 %)
   const bool wide = 2 * a.sched->fwd_chunks128 * 100 <= a.sched->fwd_chunks64 * 106;
-  auto kernel = wide ? fwd_bf16_kernel<128> : fwd_bf16_kernel<64>;
+  auto kernel = a.p.head_dim == 128 ? (wide ? fwd_bf16_kernel<128, 128> : fwd_bf16_kernel<64, 128>)
+                                    : (wide ? fwd_bf16_kernel<128, 64> : fwd_bf16_kernel<64, 64>);
   kernel<<<(unsigned)(queues ? (size_t)kNumCUs : blocks), kThreads, 0, st>>>(
       a.sched->d_q_tiles, a.sched->d_segs, a.d_kend, (const uint16_t*)a.q, (const uint16_t*)a.k,
       (const uint16_t*)a.v, (uint16_t*)a.o_out, a.lse_out, a.p.n_q_heads, a.p.n_kv_heads, a.tc.hb,

@@ -16,25 +16,12 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
-// LDS tiles hold 128 bf16 per row plus padding chosen for how the tile is read
-// (64 banks of 4 bytes).  16-byte row reads are served 16 lanes (rows) at a
-// time and need a row pitch of 4*odd banks; the transposing 8-byte reads are
-// served per 16-lane group (4 rows x 32 bytes) and need >= 8 banks between rows.
-constexpr int kHeadDim = 128;
-constexpr int kPitchRow = kHeadDim + 8;    // 68 banks  = 4 mod 64: row reads only
-constexpr int kPitchCol = kHeadDim + 32;   // 80 banks  = 16 mod 64: column (transposing) reads only
-constexpr int kPitchBoth = kHeadDim + 24;  // 76 banks  = 12 mod 64: both kinds of read
-
 // D(32x32) += A(32x16) * B(16x32), bf16 inputs, fp32 accumulate.
 // Lane l = (c = l % 32, hh = l / 32):
 //   A: row c,     k = 8*hh .. 8*hh+7        B: column c, k = 8*hh .. 8*hh+7
 //   D: column c,  row = 8*(v/4) + 4*hh + v%4   for v = 0..15
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
-}
-
-__device__ __forceinline__ bf16x8 lds_read_row8(const uint16_t* p) {
-  return *reinterpret_cast<const bf16x8*>(p);
 }
 
 // Transposing LDS read (ds_read_b64_tr_b16).  Within each group of 16 lanes,
@@ -47,29 +34,6 @@ __device__ __forceinline__ s16x4 lds_read_tr4(const uint16_t* p) {
       (s16x4 __attribute__((address_space(3)))*)(p));
 }
 
-// Operand for a matrix product that contracts over tile ROWS: for lane
-// (c, hh) returns rows {r0+4hh..r0+4hh+3, r0+8+4hh..r0+8+4hh+3} of column
-// col0 + c of a row-major LDS tile.  This row order is exactly the order in
-// which a 32x32 accumulator block hands its 8 values v = 8s..8s+7 to the next
-// product when reused as the other operand (r0 = 16*s inside the block).
-template <int PITCH>
-__device__ __forceinline__ bf16x8 lds_read_col8(const uint16_t* tile, int r0, int col0) {
-  const int l = threadIdx.x & 63;
-  const int i = l & 15, g16 = l >> 4;
-  const int hh = g16 >> 1;
-  const int col = col0 + 16 * (g16 & 1) + 4 * (i & 3);
-  const int row = r0 + 4 * hh + (i >> 2);
-  s16x4 lo = lds_read_tr4(tile + row * PITCH + col);
-  s16x4 hi = lds_read_tr4(tile + (row + 8) * PITCH + col);
-  union {
-    struct { s16x4 a, b; } s;
-    bf16x8 v;
-  } u;
-  u.s.a = lo;
-  u.s.b = hi;
-  return u.v;
-}
-
 __device__ __forceinline__ bf16x8 pack8(const f32x16& x, int s) {
   bf16x8 r;
 #pragma unroll
@@ -77,69 +41,78 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& x, int s) {
   return r;
 }
 
-// 64 rows x 128 bf16 from global (row pitch `stride` elements) into registers,
-// 16 bytes per thread per pass, NT threads; rows >= nvalid come back as zeros.
-template <int NT>
-struct TileRegs {
-  uint4 r[1024 / NT];
-};
-
-template <int NT>
-__device__ __forceinline__ void tile_load(TileRegs<NT>& t, const uint16_t* base, size_t stride,
-                                          int nvalid) {
-#pragma unroll
-  for (int i = 0; i < 1024 / NT; ++i) {
-    const int id = threadIdx.x + NT * i;
-    const int row = id >> 4, col = id & 15;
-    if (row < nvalid)
-      t.r[i] = *reinterpret_cast<const uint4*>(base + (size_t)row * stride + col * 8);
-    else
-      t.r[i] = make_uint4(0, 0, 0, 0);
-  }
-}
-
-template <int PITCH, int NT>
-__device__ __forceinline__ void tile_store(const TileRegs<NT>& t, uint16_t* lds) {
-#pragma unroll
-  for (int i = 0; i < 1024 / NT; ++i) {
-    const int id = threadIdx.x + NT * i;
-    const int row = id >> 4, col = id & 15;
-    *reinterpret_cast<uint4*>(lds + row * PITCH + col * 8) = t.r[i];
-  }
-}
-
 
 // ---- tiles filled by direct global-to-LDS loads -------------------------------
-// A wave's 16-byte direct loads land in 1 KB of consecutive LDS = 4 rows of 128
-// bf16, so padding is only possible between such 4-row groups.  Bank conflicts
-// are avoided by choosing WHICH tile row each matrix position uses: the matrix
-// products only need keys (or query rows) to sit at consistent positions, not in
-// order.  Position x (0..63) of a product uses tile row
-//     row_of_pos(x) = 4 * sigma(x & 15) + (x >> 4),  sigma(y) = 4 * (y & 3) + (y >> 2),
+// A tile is 64 rows (keys or query rows) of HD bf16, HD = 128 or 64.  A wave's
+// 16-byte direct loads land in 1 KB of consecutive LDS = 4 rows of 128 (8 rows of
+// 64) bf16, so padding is only possible between such groups of rows.  Bank
+// conflicts are avoided by choosing WHICH tile row each matrix position uses: the
+// matrix products only need keys (or query rows) to sit at consistent positions,
+// not in order.  With sigma(y) = 4 * (y & 3) + (y >> 2), position x (0..63) uses
+//     HD = 128:  group sigma(x & 15),      row (x >> 4) of the group's 4
+//     HD = 64 :  group sigma(x & 15) & 7,  row (sigma(x & 15) >> 3) + 2 * (x >> 4) of its 8
 // and group g starts at g * 1040 bytes.  Then the 16 lanes of one pass of a
-// 16-byte row read touch 16 different groups (16 different 16-byte bank offsets),
-// the 4 rows of one pass of a transposing read (32 lanes: 4 rows x 64 bytes) sit
-// 64 bytes of bank offset apart, and every read address is a per-lane base plus
-// a compile-time constant.
-constexpr int kGroupPitch = 4 * kHeadDim + 8;     // elements between 4-row groups (1040 bytes)
-constexpr int kTileElems = 16 * kGroupPitch;      // one 64 x 128 tile
+// 16-byte row read touch 16 different 16-byte bank offsets, the 4 rows of one pass
+// of a transposing read (32 lanes: 4 rows x 64 bytes) sit 64 bytes of bank offset
+// apart, and every read address is a per-lane base plus a compile-time constant,
+// the same constants for both head dimensions.
+constexpr int kGroupPitch = 512 + 8;              // elements between groups of rows (1040 bytes)
 
 __device__ __forceinline__ int sigma16(int y) { return ((y & 3) << 2) | (y >> 2); }
-__device__ __forceinline__ int row_of_pos(int x) { return 4 * sigma16(x & 15) + (x >> 4); }
-// For lane half hh, accumulator value e (0..15) of 32-position block mb holds
-// position 32*mb + 8*(e/4) + 4*hh + e%4, i.e. tile row
-__device__ __forceinline__ int row_of_acc(int mb, int e, int hh) {
-  return 16 * (e & 3) + 8 * ((e >> 2) & 1) + 4 * hh + 2 * mb + (e >> 3);
-}
 
-// Starts the copy of rows [0, 64) x 128 bf16 (global row pitch stride_bytes,
+template <int HD>
+struct TileLayout {
+  static_assert(HD == 128 || HD == 64, "head_dim 64 or 128");
+  static constexpr int kRowsPerGroup = 512 / HD;            // rows one wave-wide direct load covers
+  static constexpr int kGroups = 64 / kRowsPerGroup;        // per 64-row tile
+  static constexpr int kTileElems = kGroups * kGroupPitch;  // one 64 x HD tile
+  static constexpr int kSteps = HD / 16;                    // k-steps of a product that contracts over HD
+  static constexpr int kBlocks = HD / 32;                   // 32-wide output blocks along HD
+
+  __device__ __forceinline__ static int row_of_pos(int x) {
+    const int s = sigma16(x & 15);
+    return HD == 128 ? 4 * s + (x >> 4) : 8 * (s & 7) + (s >> 3) + 2 * (x >> 4);
+  }
+  // For lane half hh, accumulator value e (0..15) of 32-position block mb holds
+  // position 32*mb + 8*(e/4) + 4*hh + e%4, i.e. tile row
+  __device__ __forceinline__ static constexpr int row_of_acc(int mb, int e, int hh) {
+    return HD == 128 ? 16 * (e & 3) + 8 * ((e >> 2) & 1) + 4 * hh + 2 * mb + (e >> 3)
+                     : 32 * (e & 1) + 16 * ((e >> 2) & 1) + 8 * hh + ((e >> 1) & 1) + 4 * mb + 2 * (e >> 3);
+  }
+  // element offset of position x's row inside a tile
+  __device__ __forceinline__ static int pos_off(int x) {
+    const int s = sigma16(x & 15);
+    return HD == 128 ? s * kGroupPitch + (x >> 4) * 128
+                     : (s & 7) * kGroupPitch + ((s >> 3) + 2 * (x >> 4)) * 64;
+  }
+  // Per-lane element offsets into a tile; add compile-time constants per read.
+  // Row operand (lane = position c of a 32-block, half hh): 8 elements at
+  //   tile + row_lane_off() + 256 * mb + 16 * ks          (block mb, k-step ks)
+  __device__ __forceinline__ static int row_lane_off() {
+    const int l = threadIdx.x & 63, c = l & 31, hh = l >> 5;
+    return pos_off(c) + hh * 8;
+  }
+  // Column operand (contraction over positions r0 .. r0+15, r0 a multiple of 16,
+  // columns col0 .. col0+31), for tile_col8: at
+  //   tile + col_lane_off() + 128 * (r0 / 16) + col0   and   + 2 * kGroupPitch for the upper 8
+  __device__ __forceinline__ static int col_lane_off() {
+    const int l = threadIdx.x & 63, i = l & 15, g16 = l >> 4, hh = g16 >> 1;
+    return pos_off(4 * hh + (i >> 2)) + 16 * (g16 & 1) + 4 * (i & 3);
+  }
+};
+
+// Starts the copy of rows [0, 64) x HD bf16 (global row pitch stride_bytes,
 // `base` uniform over the block) into `tile`; rows >= nvalid re-read row
 // nvalid-1 (finite data the mask hides).  Completion: async_wait_all() by every
 // thread, then a block barrier.
-template <int NT>
+template <int NT, int HD>
 __device__ __forceinline__ void tile_async_load(uint16_t* tile, const uint16_t* base,
                                                 uint32_t stride_bytes, int nvalid) {
+  using TL = TileLayout<HD>;
   constexpr int NW = NT / 64;
+  constexpr int kRowShift = HD == 128 ? 4 : 3;   // lanes per row = HD / 8
+  constexpr int kPieceMask = (1 << kRowShift) - 1;
+  static_assert(TL::kGroups % NW == 0, "every wave copies the same number of row groups");
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), l = threadIdx.x & 63;
   const uint32_t tile_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)tile;
   // The base is the same for every lane; make that visible so it lands in SGPRs.
@@ -149,16 +122,17 @@ __device__ __forceinline__ void tile_async_load(uint16_t* tile, const uint16_t* 
   const uint32_t base_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(base_bits >> 32));
   const uint32_t base_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)base_bits);
   const uint64_t sbase = ((uint64_t)base_hi << 32) | (uint64_t)base_lo;
-  // lane part of the address for a full tile: row (l >> 4) of a 4-row group, piece l & 15
-  const uint32_t lane_off = (uint32_t)(l >> 4) * stride_bytes + (l & 15) * 16;
+  // lane part of the address for a full tile: row (l >> kRowShift) of a group, 16-byte piece l & kPieceMask
+  const uint32_t lane_off = (uint32_t)(l >> kRowShift) * stride_bytes + (l & kPieceMask) * 16;
 #pragma unroll
-  for (int p = 0; p < 16 / NW; ++p) {
+  for (int p = 0; p < TL::kGroups / NW; ++p) {
     const int grp = w + NW * p;
-    uint64_t gbase = sbase + (uint64_t)(4 * grp) * stride_bytes;   // scalar
+    uint64_t gbase = sbase + (uint64_t)(TL::kRowsPerGroup * grp) * stride_bytes;   // scalar
     uint32_t voff = lane_off;
     if (nvalid < 64) {   // ragged tail of an interval (uniform branch)
       gbase = sbase;
-      voff = (uint32_t)min(4 * grp + (l >> 4), nvalid - 1) * stride_bytes + (l & 15) * 16;
+      voff = (uint32_t)min(TL::kRowsPerGroup * grp + (l >> kRowShift), nvalid - 1) * stride_bytes +
+             (l & kPieceMask) * 16;
     }
     // Written as inline assembly on purpose: for the builtin form the compiler
     // drains every outstanding load before the next LDS read, which would undo
@@ -199,25 +173,12 @@ __device__ __forceinline__ void async_wait_all() {
   asm volatile("" ::: "memory");
 }
 
-// Per-lane element offsets into a tile; add compile-time constants per read.
-// Row operand (lane = position c of a 32-block, half hh): 8 elements at
-//   tile + row_lane_off() + 256 * mb + 16 * ks          (block mb, k-step ks)
-__device__ __forceinline__ int row_lane_off() {
-  const int l = threadIdx.x & 63, c = l & 31, hh = l >> 5;
-  return sigma16(c & 15) * kGroupPitch + (c >> 4) * kHeadDim + hh * 8;
-}
-// Column operand (contraction over positions r0 .. r0+15, r0 a multiple of 16,
-// columns col0 .. col0+31): same value order as lds_read_col8, at
-//   tile + col_lane_off() + 128 * (r0 / 16) + col0   and   + 2 * kGroupPitch for the upper 8
-__device__ __forceinline__ int col_lane_off() {
-  const int l = threadIdx.x & 63, i = l & 15, g16 = l >> 4, hh = g16 >> 1;
-  return sigma16(4 * hh + (i >> 2)) * kGroupPitch + 16 * (g16 & 1) + 4 * (i & 3);
-}
+// Reads at a lane pointer made from TileLayout<HD>::row_lane_off() / col_lane_off().
 __device__ __forceinline__ bf16x8 tile_row8(const uint16_t* lane_ptr, int mb, int ks) {
   return *reinterpret_cast<const bf16x8*>(lane_ptr + 256 * mb + 16 * ks);
 }
 __device__ __forceinline__ bf16x8 tile_col8(const uint16_t* lane_ptr, int r0, int col0) {
-  const uint16_t* p = lane_ptr + kHeadDim * (r0 >> 4) + col0;
+  const uint16_t* p = lane_ptr + 128 * (r0 >> 4) + col0;
   s16x4 lo = lds_read_tr4(p);
   s16x4 hi = lds_read_tr4(p + 2 * kGroupPitch);
   union {

@@ -418,7 +418,7 @@ int validate_params(const dta_attn_params_t* p) {
   if (p->dtype == DTA_F32) {
     if (p->head_dim != 64 && p->head_dim != 128) return DTA_ERR_UNSUPPORTED;
   } else if (p->dtype == DTA_BF16) {
-    if (p->head_dim != 128) return DTA_ERR_UNSUPPORTED;
+    if (p->head_dim != 64 && p->head_dim != 128) return DTA_ERR_UNSUPPORTED;
   } else {
     return DTA_ERR_UNSUPPORTED;
   }

@@ -29,7 +29,7 @@ def _setup(parent, seg, Hq, Hkv, d, dtype, seed, scale=None):
     return x, t, tree, p, scale
 
 
-@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64)])
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("f32", 64)])
 def test_staged_backward_equals_one_call_and_is_reproducible(dtype, d):
     rng = np.random.default_rng(5)
     parent, seg = random_tree(rng, 25, 300, n_roots=2)
@@ -83,7 +83,7 @@ def test_split_key_tiles_are_exercised_and_correct():
     assert rel_err(got["dq"], dQ) <= 1e-2 and rel_err(got["dk"], dK) <= 1e-2 and rel_err(got["dv"], dV) <= 1e-2
 
 
-@pytest.mark.parametrize("dtype,d,tol", [("bf16", 128, 1e-2), ("f32", 128, 1e-5)])
+@pytest.mark.parametrize("dtype,d,tol", [("bf16", 128, 1e-2), ("bf16", 64, 1e-2), ("f32", 128, 1e-5)])
 def test_negative_and_large_scale(dtype, d, tol):
     rng = np.random.default_rng(9)
     parent, seg = random_tree(rng, 12, 150)
@@ -173,7 +173,7 @@ def test_overlap_probe_runs_and_writes_every_element():
         assert bool(torch.isfinite(out).all())
 
 
-@pytest.mark.parametrize("dtype,d,Hq,Hkv", [("bf16", 128, 8, 2), ("f32", 64, 4, 2)])
+@pytest.mark.parametrize("dtype,d,Hq,Hkv", [("bf16", 128, 8, 2), ("bf16", 64, 8, 2), ("f32", 64, 4, 2)])
 def test_outputs_with_sentinel_guards_on_both_sides_stay_inside_their_rows(dtype, d, Hq, Hkv):
     """Every output (and the workspaces) is a window inside a larger allocation
     filled with a byte pattern; after forward and backward the bytes before and

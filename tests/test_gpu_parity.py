@@ -79,25 +79,39 @@ def test_fp32_degenerate_trees():
     _compare(np.array([-1] * 5), np.array([3, 70, 1, 64, 65]), 2, 1, 64, "f32", seed=4)   # forest of single nodes
 
 
+@pytest.mark.parametrize("d", [128, 64])
 @pytest.mark.parametrize("Hq,Hkv", [(4, 1), (8, 2), (2, 1), (1, 1), (3, 1), (16, 2), (32, 8), (16, 1), (5, 1)])
-def test_bf16_random_forests(Hq, Hkv):
+def test_bf16_random_forests(Hq, Hkv, d):
     rng = np.random.default_rng(99 + Hq)
     for trial in range(3):
         parent, seg = random_tree(rng, int(rng.integers(1, 40)), 90, n_roots=int(rng.integers(1, 4)))
-        _compare(parent, seg, Hq, Hkv, 128, "bf16", seed=trial)
+        _compare(parent, seg, Hq, Hkv, d, "bf16", seed=trial)
 
 
-def test_bf16_degenerate_trees():
-    _compare(np.array([-1]), np.array([1]), 4, 1, 128, "bf16", seed=1)
-    _compare(*chain_tree([1] * 9), 4, 1, 128, "bf16", seed=2)
-    _compare(*chain_tree([300, 37, 64, 128]), 4, 2, 128, "bf16", seed=3)
-    _compare(np.array([-1] * 5), np.array([3, 70, 1, 64, 65]), 4, 1, 128, "bf16", seed=4)
+@pytest.mark.parametrize("d", [128, 64])
+def test_bf16_degenerate_trees(d):
+    _compare(np.array([-1]), np.array([1]), 4, 1, d, "bf16", seed=1)
+    _compare(*chain_tree([1] * 9), 4, 1, d, "bf16", seed=2)
+    _compare(*chain_tree([300, 37, 64, 128]), 4, 2, d, "bf16", seed=3)
+    _compare(np.array([-1] * 5), np.array([3, 70, 1, 64, 65]), 4, 1, d, "bf16", seed=4)
 
 
-@pytest.mark.parametrize("cfg,shrink", [(2, 8), (3, 16), (4, 32), (5, 4)])
-def test_bf16_scaled_down_benchmark_configs(cfg, shrink):
+@pytest.mark.parametrize("cfg,shrink,d", [(2, 8, 128), (3, 16, 128), (4, 32, 128), (5, 4, 128),
+                                          (2, 8, 64), (3, 16, 64), (4, 32, 64), (5, 4, 64)])
+def test_bf16_scaled_down_benchmark_configs(cfg, shrink, d):
     """Siblings of the benchmark trees (same branching, shorter segments) checked
-    on whole tensors; two kv groups keep the oracle to seconds."""
+    on whole tensors, with the benchmark's head_dim 128 and with head_dim 64; two
+    kv groups keep the oracle to seconds."""
     parent, seg, info = scaled_config_tree(cfg, shrink)
     G = config_heads(cfg)["n_q_heads"] // config_heads(cfg)["n_kv_heads"]
-    _compare(parent, seg, 2 * G, 2, 128, "bf16", seed=info["tensor_seed"])
+    _compare(parent, seg, 2 * G, 2, d, "bf16", seed=info["tensor_seed"])
+
+
+def test_bf16_head_dim_64_long_shared_prefix_with_split_key_tiles():
+    """head_dim 64 on a tree whose prompt tiles are split into fp32 partial sums and
+    whose launches are large enough to draw work from queues: a 1500-token prompt
+    with 24 responses, whole tensors of one kv group against the oracle."""
+    rng = np.random.default_rng(64)
+    seg = np.array([1500] + [int(x) for x in rng.integers(200, 900, size=24)])
+    parent = np.array([-1] + [0] * 24)
+    _compare(parent, seg, 8, 2, 64, "bf16", seed=64)

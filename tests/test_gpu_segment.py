@@ -96,12 +96,12 @@ def test_fp32_random_forests_push_pop(d, Hq, Hkv):
         _compare(parent, seg, Hq, Hkv, d, "f32", seed=trial, chunk_block=(0, 37)[trial])
 
 
-@pytest.mark.parametrize("Hq,Hkv", [(4, 1), (8, 2), (16, 2), (3, 1)])
-def test_bf16_random_forests_push_pop(Hq, Hkv):
+@pytest.mark.parametrize("Hq,Hkv,d", [(4, 1, 128), (8, 2, 128), (16, 2, 128), (3, 1, 128), (8, 2, 64), (3, 1, 64)])
+def test_bf16_random_forests_push_pop(Hq, Hkv, d):
     rng = np.random.default_rng(987 + Hq)
     for trial in range(2):
         parent, seg = random_tree(rng, int(rng.integers(2, 16)), 400, n_roots=int(rng.integers(1, 3)))
-        _compare(parent, seg, Hq, Hkv, 128, "bf16", seed=trial, chunk_block=(0, 150)[trial])
+        _compare(parent, seg, Hq, Hkv, d, "bf16", seed=trial, chunk_block=(0, 150)[trial])
 
 
 def test_bf16_chain_with_chunked_pops_is_chunked_causal_attention():

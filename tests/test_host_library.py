@@ -142,7 +142,7 @@ def test_error_codes():
     tree = dta.tree_build([-1, 0], [3, 4])
     for bad, want in ((dta.AttnParams(4, 3, 128, 1.0, dta.BF16), -3),      # Hq % Hkv
                       (dta.AttnParams(4, 2, 96, 1.0, dta.F32), -3),        # head_dim
-                      (dta.AttnParams(4, 2, 64, 1.0, dta.BF16), -3),       # bf16 needs 128
+                      (dta.AttnParams(4, 2, 32, 1.0, dta.BF16), -3),       # head_dim 64 or 128 only
                       (dta.AttnParams(4, 2, 128, 1.0, 7), -3),             # dtype
                       (dta.AttnParams(0, 1, 128, 1.0, dta.BF16), -1),
                       (dta.AttnParams(4, 2, 128, 0.0, dta.BF16), -1),      # scale: finite, nonzero
