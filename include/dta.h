@@ -241,8 +241,10 @@ int dta_tree_attn_bwd_stages(dta_tree_t* tree, const dta_attn_params_t* params, 
  *    allocate, also resolves the scratch array's address on that device), else
  *    DTA_ERR_INVALID_ARG;
  *  - DTA_ERR_WORKSPACE, with a message on stderr, when
- *    dta_tree_attn_workspace_bytes(tree, params, 1) exceeds 160 MiB (the
- *    benchmark configurations need 35 to 130 MiB);
+ *    dta_tree_attn_workspace_bytes(tree, params, 1) exceeds 160 MiB (trees of a
+ *    few hundred thousand tokens need 35 to 130 MiB; one whose long shared
+ *    prefix is cut into many partial sums, like the 16K-token root of the deep
+ *    benchmark tree with its 468 MiB, does not fit);
  *  - every call on a GPU uses that GPU's one array, which keeps the previous
  *    call's contents: nothing in it needs to start from zero except the queue
  *    counters, which the call clears itself with a fill kernel, and calls that

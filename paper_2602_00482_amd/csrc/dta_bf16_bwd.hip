@@ -78,7 +78,8 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
     const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const uint16_t* __restrict__ d_o, const float* __restrict__ lse,
     const uint16_t* __restrict__ o, float* __restrict__ neg_delta, float* __restrict__ neg_lse_s,
-    uint16_t* __restrict__ dq, int Hq, int Hkv, int HB, int hblocks, float scale) {
+    uint16_t* __restrict__ dq, int Hq, int Hkv, int HB, int hblocks, float scale,
+    int* __restrict__ tickets, int n_items) {
   using TL = TileLayout<HD>;
   constexpr int kTileElems = TL::kTileElems, kHeadDim = HD;
   constexpr int KS = TL::kSteps;   // products per phase: k-steps over head_dim = 2 x output blocks
@@ -93,9 +94,23 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
   constexpr int kStash = KS - kReg;
   __shared__ __attribute__((aligned(16))) uint16_t stashS[kDqThreads / 64][kStash ? 2 * kStash : 1][64 * 8];
 
-  const int inner = blockIdx.x % (Hkv * hblocks);
-  const QTile tile = tiles[blockIdx.x / (Hkv * hblocks)];
-  const int g = inner % Hkv, hblk = inner / Hkv;
+  // Which (query tile, head block, kv head) this block works on.  tickets ==
+  // nullptr: the block index says so.  Otherwise every block draws ONE item from
+  // the queues (its home head's first, blockIdx mod Hkv, then the others') and the
+  // grid holds a quarter more blocks than there are items; blocks that find the
+  // queues empty leave at once.  The hardware gives every XCD the same number of
+  // blocks, so this is what lets an XCD that runs faster do more of the items
+  // (a loop over items inside the block, as in the other two kernels, costs this
+  // kernel its register allocation).
+  int item_idx = blockIdx.x / Hkv, g_idx = blockIdx.x % Hkv;
+  if (tickets != nullptr) {
+    ItemQueues queues;
+    queues.init(tickets, n_items, Hkv);
+    if (!queues.draw(reinterpret_cast<int*>(&kendS[0][0]), item_idx, g_idx, false)) return;
+    __syncthreads();   // the slot is part of kendS: nobody may still be reading it below
+  }
+  const QTile tile = tiles[item_idx / hblocks];
+  const int g = g_idx, hblk = item_idx % hblocks;
   const int G = Hq / Hkv;
   const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
   const int c = l & 31, hh = l >> 5;
@@ -679,25 +694,37 @@ int launch_bwd_bf16_hd(const LaunchArgs& a) {
     { int ls = launch_status(__func__); if (ls != DTA_OK) return ls; }
   }
   if (a.stages & DTA_BWD_DQ) {
-    dq_bf16_kernel<HD><<<(unsigned)qblocks, kDqThreads, 0, st>>>(
+    // Long blocks (at least 64 key chunks each on average) in at least 8 rounds:
+    // blocks draw their item from queues, see the kernel.  Shorter blocks would
+    // pay more for the draw (an atomic round trip before anything else can
+    // start) than the balance between XCDs gives back.
+    const size_t n_tiles = a.sched->q_tiles.size();
+    const bool draw = a.tickets != nullptr && qblocks >= 8 * (size_t)kNumCUs &&
+                      a.sched->fwd_chunks64 >= 64 * (int64_t)n_tiles && qblocks < 0x60000000u;
+    if (draw) {
+      zero_i32_kernel<<<1, 256, 0, st>>>(a.tickets, a.p.n_kv_heads);
+      { int ls = launch_status(__func__); if (ls != DTA_OK) return ls; }
+    }
+    dq_bf16_kernel<HD><<<(unsigned)(draw ? qblocks + qblocks / 4 : qblocks), kDqThreads, 0, st>>>(
         a.sched->d_q_tiles, a.sched->d_segs, a.d_kend, (const uint16_t*)a.q, (const uint16_t*)a.k,
         (const uint16_t*)a.v, (const uint16_t*)a.d_o, a.lse_in,
         fused_delta ? (const uint16_t*)a.o : nullptr, a.delta, a.lse2, (uint16_t*)a.dq,
-        a.p.n_q_heads, a.p.n_kv_heads, a.tc.hb, a.tc.hblocks, a.p.softmax_scale);
+        a.p.n_q_heads, a.p.n_kv_heads, a.tc.hb, a.tc.hblocks, a.p.softmax_scale,
+        draw ? a.tickets : nullptr, (int)(n_tiles * (size_t)a.tc.hblocks));
     { int ls = launch_status(__func__); if (ls != DTA_OK) return ls; }
   }
   if (a.stages & DTA_BWD_DKDV) {
     // One block per item, or a fixed set of resident blocks that draw the items
-    // from per-head queues.  The queues let XCDs that run faster take work from
-    // the others and save the block hand-over, at the price of a barrier pair
-    // and an atomic per item and of some L2 locality when work moves between
-    // XCDs.  Measured on MI355X (dK/dV launch, queues against blocks): forests
-    // of many short items gain (15-33 rounds of 70-160-step items +0.6...+1.5 %,
-    // up to +4 % with finer pieces), fewer than 8 rounds lose 1 % to the extra
-    // launch, and long items (1100 steps on average) lose 1.6 %.
+    // from per-head queues (the schedule decides: at least 8 rounds of items,
+    // long walks cut finer).  The queues let XCDs that run faster take work from
+    // the others (under this kernel the shader clocks of the 8 XCDs differ by up
+    // to 10 %, and one block per item gives every XCD the same share) and save
+    // the block hand-over, at the price of a barrier pair and an atomic per item.
+    // Measured on MI355X (dK/dV launch, queues against blocks): forests of many
+    // short items +0.6...+1.5 %, the 16 long answers and the deep tree +3...+5 %,
+    // fewer than 8 rounds lose 1-2 % to the extra launch.
     const size_t resident = 2 * (size_t)kNumCUs;
-    const bool queues = kblocks >= 8 * resident &&
-                        a.sched->kv_item_iters <= 512 * (int64_t)a.sched->kv_items.size();
+    const bool queues = a.sched->kv_queues && a.dk_acc == nullptr;
     int* tickets = a.tickets + a.p.n_kv_heads;   // second half: this kernel's counters
     if (queues) {
       zero_i32_kernel<<<1, 256, 0, st>>>(tickets, a.p.n_kv_heads);

@@ -82,6 +82,7 @@ struct Schedule {
   std::vector<KvReduce> kv_reduce;
   int64_t n_slots = 0;
   int64_t kv_item_iters = 0;       // sum over kv_items of (it_end - it_begin)
+  bool kv_queues = false;          // the dK/dV launch runs as resident blocks drawing items from queues
   int64_t fwd_tile_pairs = 0, bwd_tile_pairs = 0;
   // chunks the query tiles stream when every key interval is cut into pieces of 64 / 128 keys
   int64_t fwd_chunks64 = 0, fwd_chunks128 = 0;

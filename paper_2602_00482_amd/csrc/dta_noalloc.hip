@@ -12,10 +12,11 @@
 namespace {
 
 // 160 MiB per GPU, held from the moment the library's code is loaded on that GPU
-// until the process ends.  Enough for every benchmark configuration (the
-// largest, 265 672 tokens x 64 q heads, needs 130 MiB: two fp32 row statistics
-// per (token, q head), the work-queue counters and the fp32 partial sums of
-// split key tiles).
+// until the process ends: two fp32 row statistics per (token, q head), the
+// work-queue counters and the fp32 partial sums of split key tiles.  Enough for
+// trees of a few hundred thousand tokens (265 672 tokens x 64 q heads need
+// 130 MiB) unless a long shared prefix is cut into very many partial sums (the
+// deep benchmark tree with its 16K-token root needs 468 MiB and is refused).
 constexpr size_t kScratchBytes = (size_t)160 << 20;
 static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 

@@ -276,15 +276,24 @@ Schedule& get_schedule(dta_tree* tree, int bm, int bn, int hkv, int group) {
   // when cut, fp32 partial sums): with pieces of 1/4 of a slot's share the dK/dV
   // launch of the 16-response tree (configuration 2) was 5 % slower, coarser
   // ones (a whole share) let a single piece decide the end of the launch.
-  {
+  // A launch with at least 8 rounds of items runs as resident blocks that draw
+  // the items from queues and take over work from slower XCDs (see the kernel);
+  // what they can take over is whole items, so where the items are long the
+  // walks are cut four times finer (1/6 of a share): measured on the deep tree with its 128
+  // root tiles of 17 344 steps per kv head, 3 % faster than uncut walks handed
+  // out block by block, while the same queues over uncut walks are 2.5 % slower.
+  auto cut_items = [&](int64_t target_items) {
     constexpr int kChunkRows = 64;
+    s.kv_items.clear();
+    s.kv_reduce.clear();
+    s.n_slots = 0;
+    s.kv_item_iters = 0;
     auto iters_of = [&](const KvTile& t) {
       return (int64_t)((t.q_end - t.k0 + kChunkRows - 1) / kChunkRows) * group;
     };
     int64_t total = 0;
     for (const KvTile& t : s.kv_tiles) total += iters_of(t);
-    constexpr int64_t kTargetItems = 768;   // 1.5 pieces per resident block
-    const int64_t target = std::max<int64_t>(32, (total * hkv + kTargetItems - 1) / kTargetItems);
+    const int64_t target = std::max<int64_t>(32, (total * hkv + target_items - 1) / target_items);
     std::vector<int64_t> icost;
     for (const KvTile& t : s.kv_tiles) {
       const int64_t iters = iters_of(t);
@@ -314,7 +323,12 @@ Schedule& get_schedule(dta_tree* tree, int bm, int bn, int hkv, int group) {
     sorted.reserve(order.size());
     for (size_t i : order) sorted.push_back(s.kv_items[i]);
     s.kv_items.swap(sorted);
-  }
+  };
+  cut_items(768);   // 1.5 pieces per resident block
+  s.kv_queues = (int64_t)s.kv_items.size() * hkv >= 8 * 2 * (int64_t)kNumCUs;
+  // (forests of short items, under 384 steps on average, have nothing to gain from
+  // finer pieces and would only pay for more partial sums)
+  if (s.kv_queues && s.kv_item_iters > 384 * (int64_t)s.kv_items.size()) cut_items(3072);
   return tree->schedules.emplace(key, std::move(s)).first->second;
 }
 
