@@ -244,18 +244,58 @@ Schedule& get_schedule(dta_tree* tree, int bm, int bn, int hkv, int group) {
   }
   fill_first_intervals(s);
 
-  // ---- key tiles (dK/dV)
+  // ---- key tiles (dK/dV): runs of at most bn consecutive packed keys.  A block
+  // walks the union of the query ranges of its keys, [k0, max kend), so a run that
+  // mixes keys of small nodes with disjoint or much shorter ranges (leaves of a
+  // forest of short segments) keeps its four waves waiting for each other.  The
+  // cuts are therefore chosen, by dynamic programming over the packed order, to
+  // minimise the summed block time  sum over tiles of (fixed cost + walk steps):
+  // a tile either ends at a node boundary or is bn keys long.  On trees of long
+  // segments this reproduces the plain cut every bn keys.
   cost.clear();
-  for (int64_t k0 = 0; k0 < T; k0 += bn) {
-    int64_t k1 = std::min<int64_t>(T, k0 + bn);
-    int32_t mx = 0, mn = std::numeric_limits<int32_t>::max();
-    for (int64_t k = k0; k < k1; ++k) {
-      mx = std::max(mx, tree->token_kend[(size_t)k]);
-      mn = std::min(mn, tree->token_kend[(size_t)k]);
+  {
+    constexpr int64_t kChunkRows = 64, kFixedSteps = 7;   // a block's prologue and epilogue cost about 7 walk steps
+    const int64_t INF = std::numeric_limits<int64_t>::max() / 4;
+    std::vector<int64_t> best((size_t)T + 1, INF);
+    std::vector<int32_t> from((size_t)T + 1, -1);
+    best[0] = 0;
+    const std::vector<int32_t>& order = tree->dfs_order;
+    size_t rank_of_q = 0;   // DFS rank of the node that holds position q
+    for (int64_t q = 0; q < T; ++q) {
+      while (tree->node_offset[(size_t)order[rank_of_q]] + tree->seg_len[(size_t)order[rank_of_q]] <= q) ++rank_of_q;
+      const int64_t base = best[(size_t)q];
+      if (base == INF) continue;
+      int64_t mx = 0;
+      const int64_t limit = std::min<int64_t>(T, q + bn);
+      for (size_t r = rank_of_q; r < order.size(); ++r) {
+        const int32_t u = order[r];
+        const int64_t off = tree->node_offset[(size_t)u];
+        if (off >= limit) break;
+        mx = std::max(mx, off + tree->subtree_tokens[(size_t)u]);
+        // the tile ends with this node, or after bn keys inside it
+        const int64_t p = std::min(limit, off + tree->seg_len[(size_t)u]);
+        const int64_t c = base + kFixedSteps + (mx - q + kChunkRows - 1) / kChunkRows * group;
+        if (c < best[(size_t)p]) {   // (on ties the earlier start, visited first, stays)
+          best[(size_t)p] = c;
+          from[(size_t)p] = (int32_t)q;
+        }
+      }
     }
-    s.kv_tiles.push_back(KvTile{(int32_t)k0, (int32_t)k1, mx, mn, (int32_t)k0, {0, 0, 0}});
-    cost.push_back(mx - k0);
-    s.bwd_tile_pairs += (int64_t)(mx - k0) * bn;
+    std::vector<int64_t> cuts;
+    for (int64_t p = T; p > 0; p = from[(size_t)p]) cuts.push_back(p);
+    cuts.push_back(0);
+    std::reverse(cuts.begin(), cuts.end());
+    for (size_t i = 0; i + 1 < cuts.size(); ++i) {
+      const int64_t k0 = cuts[i], k1 = cuts[i + 1];
+      int32_t mx = 0, mn = std::numeric_limits<int32_t>::max();
+      for (int64_t k = k0; k < k1; ++k) {
+        mx = std::max(mx, tree->token_kend[(size_t)k]);
+        mn = std::min(mn, tree->token_kend[(size_t)k]);
+      }
+      s.kv_tiles.push_back(KvTile{(int32_t)k0, (int32_t)k1, mx, mn, (int32_t)k0, {0, 0, 0}});
+      cost.push_back(mx - k0);
+      s.bwd_tile_pairs += (int64_t)(mx - k0) * bn;
+    }
   }
   {
     std::vector<size_t> order(s.kv_tiles.size());
