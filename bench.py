@@ -231,7 +231,7 @@ class Runner:
         return {"tree_build_ms": {"median": float(np.median(b)), "min": float(np.min(b))},
                 "schedule_and_upload_ms": {"median": float(np.median(p)), "min": float(np.min(p))}}
 
-    def time_kernels(self, iters):
+    def time_kernels(self, iters, with_power=False):
         """Average duration of each launch, HIP events on the launch stream."""
         dta, torch = self.dta, self.torch
         tree = dta.tree_build(self.parent, self.seg)
@@ -244,23 +244,94 @@ class Runner:
             "dq": lambda: dta.tree_attn_bwd(*a, stages=dta.BWD_DELTA | dta.BWD_DQ),
             "dkdv": lambda: dta.tree_attn_bwd(*a, stages=dta.BWD_DKDV),
         }
-        out, out_min = {}, {}
+        out, out_min, power = {}, {}, {}
+        sampler = PowerSampler(period=0.15) if with_power else None
+        if sampler:
+            sampler.__enter__()
         for name, fn in launches.items():
             fn()
             torch.cuda.synchronize()
             ev = [torch.cuda.Event(enable_timing=True) for _ in range(iters + 1)]
+            t0 = time.time()
             ev[0].record()
             for i in range(iters):
                 fn()
                 ev[i + 1].record()
             torch.cuda.synchronize()
+            t1 = time.time()
             out[name] = ev[0].elapsed_time(ev[iters]) / iters
             out_min[name] = min(ev[i].elapsed_time(ev[i + 1]) for i in range(iters))
+            if sampler:
+                power[name] = (t0 + 0.25 * (t1 - t0), t1)
+        if sampler:
+            sampler.__exit__()
+            power = {k: sampler.summary(*v) for k, v in power.items()}
         self.kernel_ms_min = out_min
+        self.kernel_power = power if with_power else None
         info = tree.info()
         sched = tree.schedule_info(self.params)
         tree.destroy()
         return out, info, sched
+
+
+class PowerSampler:
+    """Polls `rocm-smi -a` in a thread while the GPU works: socket power, the package
+    power limit, the accumulated time the power limiter was active, and the shader
+    clock of each XCD.  What it returns says whether the kernels ran at the power limit
+    (they do: the published peak assumes 2.4 GHz, the chip settles at 1.6-1.9 GHz)."""
+
+    KEYS = ("current_socket_power", "ppt_residency_acc", "current_gfxclk")
+
+    def __init__(self, period=0.25):
+        import threading
+        self.samples, self.period, self.stop = [], period, False
+        self.thread = threading.Thread(target=self._run, daemon=True)
+
+    def _poll(self):
+        import subprocess
+        try:
+            out = subprocess.run(["/opt/rocm/bin/rocm-smi", "-a"], capture_output=True, text=True, timeout=5).stdout
+        except Exception:
+            return None
+        d = {}
+        for line in out.splitlines():
+            for key in self.KEYS + ("Max Graphics Package Power",):
+                if key in line and "XCP" not in line:
+                    d[key] = line.split(":")[-1].strip()
+        return d or None
+
+    def _run(self):
+        while not self.stop:
+            d = self._poll()
+            if d:
+                self.samples.append((time.time(), d))
+            time.sleep(self.period)
+
+    def __enter__(self):
+        self.thread.start()
+        return self
+
+    def __exit__(self, *a):
+        self.stop = True
+        self.thread.join(timeout=10)
+
+    def summary(self, t0, t1):
+        sel = [d for t, d in self.samples if t0 <= t <= t1]
+        if not sel:
+            return None
+        try:
+            power = [float(d["current_socket_power"]) for d in sel if "current_socket_power" in d]
+            clocks = [[float(x) for x in d["current_gfxclk"].strip("[]").split(",")] for d in sel if "current_gfxclk" in d]
+            ppt = [int(d["ppt_residency_acc"]) for d in sel if "ppt_residency_acc" in d]
+            cap = next((float(d["Max Graphics Package Power"]) for d in sel if "Max Graphics Package Power" in d), None)
+            mean_clk = [sum(c[i] for c in clocks) / len(clocks) for i in range(len(clocks[0]))] if clocks else None
+            return {"samples": len(sel), "socket_power_w_mean": sum(power) / len(power) if power else None,
+                    "socket_power_w_max": max(power) if power else None, "package_power_limit_w": cap,
+                    "power_limiter_active_count_delta": (ppt[-1] - ppt[0]) if len(ppt) > 1 else None,
+                    "shader_clock_mhz_per_xcd": None if mean_clk is None else [round(c) for c in mean_clk],
+                    "shader_clock_mhz_min_over_mean": None if mean_clk is None else min(mean_clk) / (sum(mean_clk) / len(mean_clk))}
+        except Exception as e:
+            return {"error": str(e)}
 
 
 def _dense_batches(rollout_lens, token_budget):
@@ -459,12 +530,22 @@ def main():
         is_leaf[parent[parent >= 0]] = False
         return (lay["node_start_depth"] + seg)[is_leaf]
 
-    def measure(cfg, steps, warmup, with_dense, with_cpu, with_segments=True):
+    def measure(cfg, steps, warmup, with_dense, with_cpu, with_segments=True, with_power=False, head_dim=None):
         parent, seg, meta = config_tree(cfg)
         heads = config_heads(cfg)
+        if head_dim is not None:
+            heads["head_dim"] = head_dim
         r = Runner(parent, seg, heads, meta["tensor_seed"])
-        sec = r.time_steps(steps, warmup)
-        kern, info, sched = r.time_kernels(max(3, min(10, steps)))
+        power = None
+        if with_power:
+            with PowerSampler() as ps:
+                t0 = time.time()
+                sec = r.time_steps(steps, warmup)
+                t1 = time.time()
+            power = ps.summary(t0 + 0.3 * (t1 - t0), t1)      # the warm-up steps are at the front
+        else:
+            sec = r.time_steps(steps, warmup)
+        kern, info, sched = r.time_kernels(max(3, min(10, steps)), with_power=with_power)
         if with_segments:
             seg_sec, seg_calls = r.time_segment_steps(max(1, min(5, steps)), 1)
             lo_sec, lo_calls = r.time_segment_steps(max(1, min(5, steps)), 1, r.leaf_order_calls(2048))
@@ -495,6 +576,9 @@ def main():
             "C_attn_leaf": info["dense_pairs"] / pairs,
             "rollout_tokens_per_s_tree": info["rollout_tokens"] / sec,
         }
+        if power is not None:
+            res["power_and_clocks_during_timed_steps"] = power
+            res["power_and_clocks_per_kernel"] = r.kernel_power
         if with_segments:
             # the same fwd+bwd issued one segment at a time in the paper's push / pop
             # order (2 calls per node, dK/dV accumulated in fp32 across calls)
@@ -519,7 +603,8 @@ def main():
         return res, kern, info, heads, cpu
 
     main_res, kern, info, heads, cpu = measure(args.config, args.steps, args.warmup,
-                                               not args.no_dense, not args.no_cpu, not args.no_segments)
+                                               not args.no_dense, not args.no_cpu, not args.no_segments,
+                                               with_power=True)
     Hq, d = heads["n_q_heads"], heads["head_dim"]
     peak = PEAK_TFLOPS[heads["dtype"]]
     pairs_h = info["unique_pairs"] * Hq
@@ -564,6 +649,11 @@ def main():
             continue
         res, *_ = measure(c, max(2, min(5, args.steps)), 1, not args.no_dense, False, not args.no_segments)
         others[WORKLOAD_NAMES[c]] = res
+    if others and 3 in [int(x) for x in args.others.split(",") if x.strip()]:
+        # the same kernels instantiated for head_dim 64 (not a BASELINE configuration): the
+        # multi-turn forest's tree with 64-wide heads, kernel times only
+        res, *_ = measure(3, 3, 1, False, False, False, head_dim=64)
+        others[WORKLOAD_NAMES[3] + "_head_dim_64"] = res
     if others:
         line["other_configs"] = others
     print(json.dumps(line))

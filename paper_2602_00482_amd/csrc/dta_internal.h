@@ -113,7 +113,7 @@ struct dta_tree {
   // schedules keyed by (bm, bn, kv heads, group size)
   std::map<uint64_t, dta::Schedule> schedules;
   // schedules of segment calls, keyed by (tile configuration, t_begin, t_end): at most
-  // dta::kMaxSegmentSchedules of them; beyond that the least recently used one is dropped
+  // dta::max_segment_schedules(n_nodes) of them; beyond that the least recently used one is dropped
   // and its device block waits in `retired` for the next schedule that fits into it
   std::map<std::array<uint64_t, 3>, dta::Schedule> segment_schedules;
   uint64_t use_counter = 0;
@@ -129,9 +129,13 @@ struct dta_tree {
 
 namespace dta {
 
-// Segment schedules a tree keeps (an executor walks a tree's segments over and over, one
-// schedule per distinct row range; 2 x nodes ranges in the push / pop order).
-constexpr size_t kMaxSegmentSchedules = 1024;
+// Segment schedules a tree keeps: an executor walks a tree's segments over and over, one
+// schedule per distinct row range.  The push / pop order has one range per node and chunked
+// pops a few more, so the bound grows with the tree: max(1024, 4 x nodes + 64).
+inline size_t max_segment_schedules(int32_t n_nodes) {
+  const size_t by_nodes = 4 * (size_t)n_nodes + 64;
+  return by_nodes > 1024 ? by_nodes : 1024;
+}
 
 // Resident blocks of a launch whose blocks draw work items from queues: the
 // 256 CUs of an MI355X times the blocks of that kernel that fit on a CU.

@@ -450,7 +450,7 @@ Schedule& get_segment_schedule(dta_tree* tree, int bm, int bn, int hkv, int grou
   // keep the cache bounded: drop the least recently used schedule; its device
   // block may still be read by a launch in flight, so it is only set aside here
   // (whoever uploads into it next orders that copy behind the tree's launches)
-  if (tree->segment_schedules.size() >= kMaxSegmentSchedules) {
+  if (tree->segment_schedules.size() >= max_segment_schedules(tree->n_nodes)) {
     auto lru = tree->segment_schedules.begin();
     for (auto e = tree->segment_schedules.begin(); e != tree->segment_schedules.end(); ++e)
       if (e->second.last_used < lru->second.last_used) lru = e;

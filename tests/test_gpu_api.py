@@ -213,8 +213,9 @@ def test_outputs_with_sentinel_guards_on_both_sides_stay_inside_their_rows(dtype
 
 
 def test_more_segment_ranges_than_the_schedule_cache_holds():
-    """A tree keeps at most 1024 segment schedules; beyond that the least recently
-    used one is dropped and its device block is reused.  1300 one-row forward
+    """A tree keeps at most max(1024, 4 x nodes + 64) segment schedules (1024 for this
+    one-node tree); beyond that the least recently used one is dropped and its
+    device block is reused.  1300 one-row forward
     calls, then the first rows again (their schedules are gone and are rebuilt
     into recycled blocks): all rows must equal the one-launch forward."""
     T = 1300
