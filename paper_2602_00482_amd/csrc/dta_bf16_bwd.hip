@@ -320,14 +320,14 @@ __global__ __launch_bounds__(kDqThreads) void dq_bf16_kernel(
   }
 }
 
-constexpr int kKvThreads = 256;
-constexpr int kKvTile = 128;   // keys per dK/dV tile (32 per wave)
-
-// Key-stationary dK/dV: 4 waves, 32 key columns each, K and V rows in
-// registers.  Two blocks share a CU (everything fits in 256 registers), so one
-// block's global loads and barriers are covered by the other's matrix work.
-template <int HD>
-__global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
+// Key-stationary dK/dV: NW waves, 32 key columns each, K and V rows in
+// registers.  NW = 4 (tiles of 128 keys): two blocks share a CU (everything
+// fits in 256 registers), so one block's global loads and barriers are covered
+// by the other's matrix work.  NW = 8 (tiles of 256 keys, schedules of long
+// walks): one block per CU, and every 64-row chunk copied into LDS meets twice
+// the keys.
+template <int HD, int NW>
+__global__ __launch_bounds__(64 * NW, 8 / NW) void dkdv_bf16_kernel(
     const KvItem* __restrict__ items, const int32_t* __restrict__ kend,
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, const uint16_t* __restrict__ d_o,
@@ -338,6 +338,7 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
   using TL = TileLayout<HD>;
   constexpr int kTileElems = TL::kTileElems, kHeadDim = HD;
   constexpr int KS = TL::kSteps, DB = TL::kBlocks;
+  constexpr int kKvThreads = 64 * NW, kKvTile = 32 * NW;
   // One object, so that every tile read is "per-lane base + compile-time offset".
   // With head_dim 128 the last k-steps of this wave's K and V operands (kStashK
   // and kStashV of the 8) live in LDS instead of registers, and so do the
@@ -351,14 +352,14 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
     uint16_t Q[2][kTileElems];
     uint16_t dO[2][kTileElems];
     float stat[2][2][kBQ];   // [buffer][-lse/scale | -delta][position]
-    uint16_t stash[4][kStashK + kStashV ? kStashK + kStashV : 1][64 * 8];
+    uint16_t stash[NW][kStashK + kStashV ? kStashK + kStashV : 1][64 * 8];
     int2 bound[kKvThreads];
   };
   __shared__ __attribute__((aligned(256))) Smem sm;
   // The drawn item travels through two words of the second statistics buffer:
   // nothing writes that buffer between the barrier at the end of an item and the
-  // first barrier of the next item's walk, and the block's LDS must stay at
-  // exactly 80 KB for two blocks to fit on a CU.
+  // first barrier of the next item's walk, and with four waves the block's LDS
+  // must stay at exactly 80 KB for two blocks to fit on a CU.
   int* next_item = reinterpret_cast<int*>(&sm.stat[1][0][0]);
 
   // Which (work item, kv head) this block works on.  tickets == nullptr: the
@@ -415,7 +416,8 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
   // key tiles of one node share the end of their query range, and k0 is a
   // multiple of the chunk size, so blocks that start together read exactly the
   // same 64-row chunks at the same time and find them in L2.  Step `it` lives
-  // in buffer it & 1 and is copied global -> LDS one iteration ahead of its use
+  // in buffer (it - it_begin) & 1 and is copied global -> LDS one iteration ahead of its use
+  // (a third buffer and two iterations ahead, which the eight-wave form has the LDS for, is 1 % slower)
   // (this item covers iterations [it_begin, it_end) of the tile's walk)
   const int n_chunks = (tile.q_end - tile.q_begin + kBQ - 1) / kBQ;
   const int total = tile.it_end;
@@ -576,7 +578,7 @@ __global__ __launch_bounds__(kKvThreads, 2) void dkdv_bf16_kernel(
   if (tickets != nullptr) queues.prefetch();
 
   if (tile.slot >= 0) {
-    // one of several items of this key tile: fp32 partial sums, [dK | dV] x 128 keys x 128
+    // one of several items of this key tile: fp32 partial sums, [dK | dV] x keys of a tile x head_dim
     float* pk = partial + ((size_t)tile.slot * Hkv + g) * (2 * kKvTile * kHeadDim) +
                 (size_t)(32 * w + c) * kHeadDim + 4 * hh;
     float* pv = pk + kKvTile * kHeadDim;
@@ -642,8 +644,8 @@ __global__ __launch_bounds__(256) void dkdv_reduce_kernel(const KvReduce* __rest
                                                           const float* __restrict__ partial,
                                                           uint16_t* __restrict__ dk,
                                                           uint16_t* __restrict__ dv, int Hkv,
-                                                          float scale) {
-  // 8 blocks per (tile, kv head), 16 keys each, so that even a handful of split
+                                                          float scale, int kKvTile) {
+  // 8 blocks per (tile, kv head), an eighth of the tile's kKvTile keys each, so that even a handful of split
   // tiles fills the chip
   const int sub = blockIdx.x & 7;
   const KvReduce r = red[(blockIdx.x >> 3) / Hkv];
@@ -723,14 +725,17 @@ int launch_bwd_bf16_hd(const LaunchArgs& a) {
     // Measured on MI355X (dK/dV launch, queues against blocks): forests of many
     // short items +0.6...+1.5 %, the 16 long answers and the deep tree +3...+5 %,
     // fewer than 8 rounds lose 1-2 % to the extra launch.
-    const size_t resident = 2 * (size_t)kNumCUs;
+    const bool wide = a.sched->kv_keys == 256;   // tiles of 256 keys: eight waves, one block per CU
+    if (a.sched->kv_keys != 128 && !wide) return DTA_ERR_UNSUPPORTED;
+    const size_t resident = (wide ? 1 : 2) * (size_t)kNumCUs;
     const bool queues = a.sched->kv_queues && a.dk_acc == nullptr;
     int* tickets = a.tickets + a.p.n_kv_heads;   // second half: this kernel's counters
     if (queues) {
       zero_i32_kernel<<<1, 256, 0, st>>>(tickets, a.p.n_kv_heads);
       { int ls = launch_status(__func__); if (ls != DTA_OK) return ls; }
     }
-    dkdv_bf16_kernel<HD><<<(unsigned)(queues ? resident : kblocks), kKvThreads, 0, st>>>(
+    auto kernel = wide ? dkdv_bf16_kernel<HD, 8> : dkdv_bf16_kernel<HD, 4>;
+    kernel<<<(unsigned)(queues ? resident : kblocks), wide ? 512 : 256, 0, st>>>(
         a.sched->d_kv_items, a.d_kend, (const uint16_t*)a.q, (const uint16_t*)a.k,
         (const uint16_t*)a.v, (const uint16_t*)a.d_o, a.lse2, a.delta, (uint16_t*)a.dk,
         (uint16_t*)a.dv, a.partial, a.dk_acc, a.dv_acc, a.p.n_q_heads, a.p.n_kv_heads,
@@ -739,7 +744,7 @@ int launch_bwd_bf16_hd(const LaunchArgs& a) {
     if (!a.sched->kv_reduce.empty()) {
       dkdv_reduce_kernel<HD><<<(unsigned)(a.sched->kv_reduce.size() * a.p.n_kv_heads * 8), 256, 0, st>>>(
           a.sched->d_kv_reduce, a.partial, (uint16_t*)a.dk, (uint16_t*)a.dv, a.p.n_kv_heads,
-          a.p.softmax_scale);
+          a.p.softmax_scale, a.sched->kv_keys);
       { int ls = launch_status(__func__); if (ls != DTA_OK) return ls; }
     }
   }

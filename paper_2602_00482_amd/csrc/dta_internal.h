@@ -74,6 +74,7 @@ struct KvReduce {
 // dispatcher, which hands out blocks in index order, balances the CUs.
 struct Schedule {
   int bm = 0, bn = 0;
+  int kv_keys = 0;   // keys per dK/dV tile in this schedule: bn, or 2*bn where the walks are long
   std::vector<QTile> q_tiles;
   std::vector<KeySeg> segs;
   std::vector<KvTile> kv_tiles;
@@ -140,6 +141,8 @@ inline size_t max_segment_schedules(int32_t n_nodes) {
 // Resident blocks of a launch whose blocks draw work items from queues: the
 // 256 CUs of an MI355X times the blocks of that kernel that fit on a CU.
 constexpr int kNumCUs = 256;
+// Key tiles of 256 keys (eight-wave dK/dV blocks) for schedules of long walks.
+constexpr bool wide_key_tiles = true;
 
 // Key of a whole-tree schedule in dta_tree::schedules.
 inline uint64_t schedule_key(int bm, int bn, int hkv, int group) {

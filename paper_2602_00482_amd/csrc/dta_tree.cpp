@@ -180,7 +180,7 @@ void fill_first_intervals(Schedule& s) {
 }  // namespace
 
 size_t partial_bytes(const Schedule& s) {
-  return (size_t)s.n_slots * (size_t)s.hkv * 2u * (size_t)s.bn * 128u * sizeof(float);
+  return (size_t)s.n_slots * (size_t)s.hkv * 2u * (size_t)s.kv_keys * 128u * sizeof(float);
 }
 
 Schedule& get_schedule(dta_tree* tree, int bm, int bn, int hkv, int group) {
@@ -252,8 +252,11 @@ Schedule& get_schedule(dta_tree* tree, int bm, int bn, int hkv, int group) {
   // minimise the summed block time  sum over tiles of (fixed cost + walk steps):
   // a tile either ends at a node boundary or is bn keys long.  On trees of long
   // segments this reproduces the plain cut every bn keys.
-  cost.clear();
-  {
+  auto cut_key_tiles = [&](int keys) {
+    cost.clear();
+    s.kv_tiles.clear();
+    s.bwd_tile_pairs = 0;
+    s.kv_keys = keys;
     constexpr int64_t kChunkRows = 64, kFixedSteps = 7;   // a block's prologue and epilogue cost about 7 walk steps
     const int64_t INF = std::numeric_limits<int64_t>::max() / 4;
     std::vector<int64_t> best((size_t)T + 1, INF);
@@ -266,7 +269,7 @@ Schedule& get_schedule(dta_tree* tree, int bm, int bn, int hkv, int group) {
       const int64_t base = best[(size_t)q];
       if (base == INF) continue;
       int64_t mx = 0;
-      const int64_t limit = std::min<int64_t>(T, q + bn);
+      const int64_t limit = std::min<int64_t>(T, q + keys);
       for (size_t r = rank_of_q; r < order.size(); ++r) {
         const int32_t u = order[r];
         const int64_t off = tree->node_offset[(size_t)u];
@@ -294,24 +297,23 @@ Schedule& get_schedule(dta_tree* tree, int bm, int bn, int hkv, int group) {
       }
       s.kv_tiles.push_back(KvTile{(int32_t)k0, (int32_t)k1, mx, mn, (int32_t)k0, {0, 0, 0}});
       cost.push_back(mx - k0);
-      s.bwd_tile_pairs += (int64_t)(mx - k0) * bn;
+      s.bwd_tile_pairs += (int64_t)(mx - k0) * keys;
     }
-  }
-  {
-    std::vector<size_t> order(s.kv_tiles.size());
-    std::iota(order.begin(), order.end(), 0);
-    std::stable_sort(order.begin(), order.end(),
+    std::vector<size_t> by_cost(s.kv_tiles.size());
+    std::iota(by_cost.begin(), by_cost.end(), 0);
+    std::stable_sort(by_cost.begin(), by_cost.end(),
                      [&](size_t a, size_t b) { return order_key(cost[a]) > order_key(cost[b]); });
     std::vector<KvTile> sorted;
-    sorted.reserve(order.size());
-    for (size_t i : order) sorted.push_back(s.kv_tiles[i]);
+    sorted.reserve(by_cost.size());
+    for (size_t i : by_cost) sorted.push_back(s.kv_tiles[i]);
     s.kv_tiles.swap(sorted);
-  }
+  };
+  cut_key_tiles(bn);
 
   // ---- dK/dV launch items: cut the longest walks so that no block becomes the
-  // critical path.  The chip holds 512 blocks of this kernel; a piece of a cut
-  // walk is at most 2/3 of the work one of those slots gets on average, and only
-  // walks longer than that are cut.  Finer pieces balance no better and cost
+  // critical path.  The chip holds `resident` blocks of this kernel (512 of four
+  // waves, 256 of eight); a piece of a cut walk is at most 2/3 of the work one of
+  // those slots gets on average, and only walks longer than that are cut.  Finer pieces balance no better and cost
   // more (every item pays its prologue, the masked steps of its diagonal and,
   // when cut, fp32 partial sums): with pieces of 1/4 of a slot's share the dK/dV
   // launch of the 16-response tree (configuration 2) was 5 % slower, coarser
@@ -364,11 +366,28 @@ Schedule& get_schedule(dta_tree* tree, int bm, int bn, int hkv, int group) {
     for (size_t i : order) sorted.push_back(s.kv_items[i]);
     s.kv_items.swap(sorted);
   };
-  cut_items(768);   // 1.5 pieces per resident block
-  s.kv_queues = (int64_t)s.kv_items.size() * hkv >= 8 * 2 * (int64_t)kNumCUs;
-  // (forests of short items, under 384 steps on average, have nothing to gain from
-  // finer pieces and would only pay for more partial sums)
-  if (s.kv_queues && s.kv_item_iters > 384 * (int64_t)s.kv_items.size()) cut_items(3072);
+  // items for a launch shape that keeps `resident` blocks on the chip
+  auto cut_for = [&](int64_t resident) {
+    cut_items(resident * 3 / 2);
+    s.kv_queues = (int64_t)s.kv_items.size() * hkv >= 8 * resident;
+    // (forests of short items, under 384 steps on average, have nothing to gain from
+    // finer pieces and would only pay for more partial sums)
+    if (s.kv_queues && s.kv_item_iters > 384 * (int64_t)s.kv_items.size()) cut_items(resident * 6);
+  };
+  cut_for(2 * (int64_t)kNumCUs);
+  constexpr int64_t kWideMinIters = 96;
+  if (bn == 128 && wide_key_tiles && s.kv_item_iters > kWideMinIters * (int64_t)s.kv_items.size()) {
+    // Long walks (96 steps per item and more): tiles of 256 keys for the
+    // eight-wave form of the kernel, one block per CU.  Every streamed 64-row
+    // chunk then meets twice the keys, which halves the copies L2 -> LDS per
+    // product; the steps of a walk, and so the piece lengths in steps, stay what
+    // they are with 128 keys.  Measured on MI355X (dK/dV launch): the deep tree
+    // -3.8 %, the multi-turn forest -2 %, 16 long answers -1.3 %; forests of short
+    // segments are cut at node boundaries either way and do not change (+-0.5 %),
+    // so the threshold only keeps them on the two-blocks-per-CU form.
+    cut_key_tiles(256);
+    cut_for((int64_t)kNumCUs);
+  }
   return tree->schedules.emplace(key, std::move(s)).first->second;
 }
 
@@ -385,6 +404,7 @@ Schedule& get_segment_schedule(dta_tree* tree, int bm, int bn, int hkv, int grou
   s.last_used = ++tree->use_counter;
   s.bm = bm;
   s.bn = bn;
+  s.kv_keys = bn;
   s.hkv = hkv;
   s.group = group;
 
@@ -555,7 +575,7 @@ int dta_tree_schedule_info(dta_tree_t* tree, const dta_attn_params_t* params,
     out->fwd_q_tile_tokens = tc.bm;
     out->fwd_work_items = (int64_t)s.q_tiles.size();
     out->fwd_tile_pairs = s.fwd_tile_pairs;
-    out->bwd_kv_tile_tokens = tc.bn;
+    out->bwd_kv_tile_tokens = s.kv_keys;
     out->bwd_work_items = (int64_t)s.kv_items.size();
     out->bwd_tile_pairs = s.bwd_tile_pairs;
     out->metadata_bytes =

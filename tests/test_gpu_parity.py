@@ -107,6 +107,25 @@ def test_bf16_scaled_down_benchmark_configs(cfg, shrink, d):
     _compare(parent, seg, 2 * G, 2, d, "bf16", seed=info["tensor_seed"])
 
 
+@pytest.mark.parametrize("d", [128, 64])
+def test_bf16_long_walks_on_256_key_tiles(d):
+    """A tree whose key tiles walk far enough for the schedule to choose tiles of
+    256 keys (the eight-wave form of the dK/dV kernel, pieces of split walks in
+    fp32 partial sums; the full-size tests run the same form under queues): a ragged
+    5963-token prompt with five long responses, whole tensors of every head
+    against the oracle.  Segment lengths are not multiples of the tile size, so
+    tiles straddle node boundaries and end in ragged tails."""
+    import paper_2602_00482_amd as dta
+    rng = np.random.default_rng(256 + d)
+    seg = np.array([5963] + [int(x) for x in rng.integers(2200, 2800, size=5)])
+    parent = np.array([-1] + [0] * 5)
+    tree = dta.tree_build(parent, seg)
+    sch = tree.schedule_info(dta.AttnParams(8, 2, d, 1.0 / math.sqrt(d), dta.BF16))
+    tree.destroy()
+    assert sch["bwd_kv_tile_tokens"] == 256, sch
+    _compare(parent, seg, 8, 2, d, "bf16", seed=256 + d)
+
+
 def test_bf16_head_dim_64_long_shared_prefix_with_split_key_tiles():
     """head_dim 64 on a tree whose prompt tiles are split into fp32 partial sums and
     whose launches are large enough to draw work from queues: a 1500-token prompt
