@@ -375,16 +375,17 @@ Schedule& get_schedule(dta_tree* tree, int bm, int bn, int hkv, int group) {
     if (s.kv_queues && s.kv_item_iters > 384 * (int64_t)s.kv_items.size()) cut_items(resident * 6);
   };
   cut_for(2 * (int64_t)kNumCUs);
-  constexpr int64_t kWideMinIters = 96;
-  if (bn == 128 && wide_key_tiles && s.kv_item_iters > kWideMinIters * (int64_t)s.kv_items.size()) {
-    // Long walks (96 steps per item and more): tiles of 256 keys for the
+  constexpr int64_t kWideMinIters = 256;
+  if (bn == 128 && wide_key_tiles && s.kv_item_iters > kWideMinIters * (int64_t)s.kv_tiles.size()) {
+    // Long walks (256 steps per 128-key tile and more): tiles of 256 keys for the
     // eight-wave form of the kernel, one block per CU.  Every streamed 64-row
     // chunk then meets twice the keys, which halves the copies L2 -> LDS per
     // product; the steps of a walk, and so the piece lengths in steps, stay what
     // they are with 128 keys.  Measured on MI355X (dK/dV launch): the deep tree
-    // -3.8 %, the multi-turn forest -2 %, 16 long answers -1.3 %; forests of short
-    // segments are cut at node boundaries either way and do not change (+-0.5 %),
-    // so the threshold only keeps them on the two-blocks-per-CU form.
+    // -3.8 %, the multi-turn forest (374 steps per tile) -2 %, 16 long answers
+    // -1.3 %; forests of short segments (130 steps per tile and fewer) take the
+    // same time either way (+-0.5 %) with more of the block's waves idle, so
+    // they stay on the two-blocks-per-CU form.
     cut_key_tiles(256);
     cut_for((int64_t)kNumCUs);
   }
