@@ -72,7 +72,7 @@ def _subtree_nodes(parent, root):
     return out
 
 
-@pytest.mark.parametrize("cfg", [2, 3, 4, 5, 6, 7])
+@pytest.mark.parametrize("cfg", [2, 3, 4, 5, 6, 7, 8])
 def test_full_size_sampled_rows_and_invariants(cfg):
     parent, seg, (Hq, Hkv, d, scale), t = _run(cfg)
     G = Hq // Hkv
@@ -140,6 +140,8 @@ def test_full_size_sampled_rows_and_invariants(cfg):
         sub_tok = {u: sum(int(seg[x]) for x in _subtree_nodes(parent, u)) for u in cands}
     cands = [u for u in cands if 1 < len(_subtree_nodes(parent, u)) and sub_tok[u] <= 6000] or \
             [u for u in cands if sub_tok[u] <= 6000]
+    if not cands:   # every subtree is larger (16 answers of 16K tokens): dK, dV are covered by the per-key test below
+        return
     root = max(cands, key=lambda u: sub_tok[u])
     nodes = _subtree_nodes(parent, root)
     keep, remap, sub_off, tok, _, _, _, dK, dV = oracle_on(nodes)
@@ -243,8 +245,9 @@ def _shared_prefix_keys(parent, seg, rng):
     keys of the root with the largest subtree (two key tiles of the dK/dV
     schedule, the longest walks of the launch), 96 keys across the end of that
     root's segment and the start of its first child, 64 keys from the middle of
-    the root, the first 40 keys of up to three other roots, and 64 keys of a
-    random interior node."""
+    the root, the first 40 keys of up to three other roots, 64 keys of a random
+    interior node, 64 keys from the middle of the longest leaf and the last 40
+    keys of the packed order."""
     off, T = L.node_offsets(parent, seg)
     _, kids = L.children_lists(parent)
     sub = {}
@@ -263,10 +266,18 @@ def _shared_prefix_keys(parent, seg, rng):
     if interior:
         u = int(rng.choice(interior))
         keys.update(range(int(off[u]), int(off[u]) + min(64, int(seg[u]))))
+    # keys whose queries are only the rest of their own segment: 64 from the middle of
+    # the longest leaf (diagonal tiles and what follows them), and the last 40 keys of
+    # the packed order (the ragged tail of the last key tile)
+    leaves = [u for u in range(len(parent)) if not kids[u]]
+    u = max(leaves, key=lambda x: int(seg[x]))
+    mid = int(off[u]) + int(seg[u]) // 2
+    keys.update(range(mid, min(int(off[u]) + int(seg[u]), mid + 64)))
+    keys.update(range(max(0, T - 40), T))
     return np.array(sorted(keys), dtype=np.int64)
 
 
-@pytest.mark.parametrize("cfg", [2, 3, 4, 5])
+@pytest.mark.parametrize("cfg", [2, 3, 4, 5, 8])
 def test_full_size_shared_prefix_key_gradients(cfg):
     """dK and dV of shared-prefix keys, element by element, against the per-key
     oracle summed over EVERY query that sees them (for a root key: all tokens of
